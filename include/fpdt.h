@@ -1,0 +1,152 @@
+/*
+ * fpdt.h -- C ABI of the MI355X chunked causal attention library (libfpdt.so).
+ *
+ * One GPU's head share of the paper's sequence-chunked distributed attention
+ * (Sec. 4.1 forward, Sec. 4.2 backward): the sequence of S tokens is cut into
+ * u = S / chunk chunks; query chunk m attends the key/value chunks i <= m one
+ * chunk pair at a time with online-softmax accumulation, the causal mask is
+ * applied on diagonal pairs only, and key/value chunks that are not in use may
+ * live in pinned host memory and are prefetched back through a double buffer
+ * while earlier pairs compute (Sec. 4.2, double buffering).  The result is
+ * ordinary causal softmax attention, O = softmax(scale * Q K^T) V, and its
+ * gradients.
+ *
+ * Conventions common to every entry point
+ *   - batch 1; tensors are row-major contiguous [S, H, D] ("token, head,
+ *     channel"), so that one chunk of a tensor is one contiguous slab;
+ *     Q, O, dO, dQ have Hq heads, K, V, dK, dV have Hkv heads; query head h
+ *     reads KV head h / (Hq / Hkv) (grouped-query attention) and the gradient
+ *     of a KV head is the sum over its query heads.
+ *   - LSE is the natural-log log-sum-exp of the scaled scores, fp32, [Hq, S].
+ *   - dtype FPDT_DTYPE_BF16: tensors are bfloat16, arithmetic is bf16 MFMA with
+ *     fp32 accumulation; FPDT_DTYPE_F32: tensors and arithmetic are fp32.
+ *   - "device" pointers are HIP device memory of the current device; "host"
+ *     pointers must be pinned (hipHostMalloc) memory.  The caller owns every
+ *     buffer.  The library allocates no device memory; it lazily creates one
+ *     side stream and a few events per process for the offload pipeline.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work: everything is ordered after prior work on
+ *     `stream` and is complete when `stream` is.  Buffers (host ones included)
+ *     must stay valid and untouched until then.
+ *   - Every function returns an fpdt_status; nothing throws or aborts.  On any
+ *     error other than FPDT_ERR_HIP nothing has been enqueued.  Text for the
+ *     last error of the calling thread: fpdt_last_error().
+ */
+#ifndef FPDT_H
+#define FPDT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FPDT_OK = 0,
+    FPDT_ERR_INVALID_ARG = 1, /* null pointer, S<=0, chunk<=0, S % chunk != 0, Hq % Hkv != 0,
+                                 scale not finite or <= 0, unknown dtype or flag bits, both
+                                 loop-order flags                                            */
+    FPDT_ERR_UNSUPPORTED = 2, /* D not in {64, 80, 128}; bf16 chunk not a multiple of
+                                 FPDT_CHUNK_MULTIPLE; fp32 with offload flags; sizes beyond
+                                 the 32-bit launch limits                                    */
+    FPDT_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned (256 B) or too small             */
+    FPDT_ERR_HIP = 4          /* a HIP runtime call failed; see fpdt_last_error()            */
+} fpdt_status;
+
+enum { FPDT_DTYPE_F32 = 0, FPDT_DTYPE_BF16 = 1 };
+
+/* chunk (and therefore S) must be a multiple of this for bf16; fp32 accepts any chunk. */
+enum { FPDT_CHUNK_MULTIPLE = 256 };
+
+enum {
+    /* K, V (forward and backward) and dK, dV (backward) are pinned HOST pointers; the
+     * library keeps at most two key/value chunks on the device (Sec. 4.1: only the
+     * chunks in use are in HBM; Sec. 4.2: double buffer).                              */
+    FPDT_KV_ON_HOST = 1u << 0,
+    /* Q, O, dO, dQ and LSE are pinned HOST pointers as well (forward: Q in, O and LSE
+     * out; backward: Q, O, dO, LSE in, dQ out) and are streamed chunk by chunk
+     * (Sec. 4.1: q, k, v chunks are offloaded once the forward is done with them).     */
+    FPDT_ACT_ON_HOST = 1u << 1,
+    /* Backward chunk-pair loop order (Sec. 4.2).  KV_OUTER is the paper's: outer loop
+     * over key/value chunks j, inner over query chunks i >= j.  Q_OUTER: outer over
+     * query chunks i, inner over j <= i.  Neither bit: the library picks
+     * (KV_OUTER unless FPDT_ACT_ON_HOST is set; FPDT_ACT_ON_HOST with KV_OUTER is
+     * FPDT_ERR_UNSUPPORTED).                                                           */
+    FPDT_BWD_KV_OUTER = 1u << 2,
+    FPDT_BWD_Q_OUTER = 1u << 3,
+    /* Run the chunk-pair schedule launch by launch (carried fp32 state between pairs)
+     * even when every tensor is resident.  Without this bit and without offload flags
+     * the bf16 path walks the same chunk pairs inside one launch per kernel.  The
+     * offload pipeline always runs pair by pair, with the same kernels in the same
+     * order as this mode: the two agree bit for bit.  fp32 always runs pair by pair.  */
+    FPDT_PAIRWISE = 1u << 4
+};
+
+/*
+ * Bytes of device workspace fpdt_attn_fwd (is_bwd = 0) or fpdt_attn_bwd (is_bwd = 1)
+ * needs for these arguments; 0 if the arguments are invalid or unsupported (call the
+ * entry point itself for the status).  With FPDT_KV_ON_HOST the forward workspace
+ * holds two key/value chunk buffers plus per-chunk state: it does not grow with S.
+ */
+size_t fpdt_attn_workspace_bytes(int64_t S, int64_t chunk, int Hq, int Hkv, int D, int dtype,
+                                 unsigned flags, int is_bwd);
+
+/*
+ * Forward (Sec. 4.1, Figs. 4-5).  For every query chunk m = 0..u-1, fold in the
+ * key/value chunks i = 0..m (earlier chunks first, the masked diagonal pair last),
+ * carrying the running row maximum, row sum and un-normalised output in fp32, and
+ * normalise once at the end of the chunk.
+ *   Q [S,Hq,D], K, V [S,Hkv,D]  in   (device; host per the flags)
+ *   O [S,Hq,D], LSE [Hq,S] fp32 out  (device; host with FPDT_ACT_ON_HOST)
+ *   workspace: device memory, 256-byte aligned, >= fpdt_attn_workspace_bytes(..., 0)
+ */
+int fpdt_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE, int64_t S,
+                  int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype, unsigned flags,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward (Sec. 4.2, Fig. 7; operand set of Sec. 3.1).  Computes
+ * Delta = rowsum(dO * O) once, then for every chunk pair (i >= j), in the chosen loop
+ * order, recomputes p = exp(scale q k^T - LSE) (masked on diagonal pairs) and adds
+ * the pair's share to dQ_i, dK_j, dV_j in fp32; gradients are rounded to the tensor
+ * dtype once a chunk's accumulation is complete.
+ *   Q, O, dO [S,Hq,D], K, V [S,Hkv,D], LSE [Hq,S]  in   (O, LSE as written by the forward)
+ *   dQ [S,Hq,D], dK, dV [S,Hkv,D]                  out  (fully overwritten)
+ *   workspace: device memory, 256-byte aligned, >= fpdt_attn_workspace_bytes(..., 1)
+ */
+int fpdt_attn_bwd(const void *Q, const void *K, const void *V, const void *O, const float *LSE,
+                  const void *dO, void *dQ, void *dK, void *dV, int64_t S, int64_t chunk, int Hq,
+                  int Hkv, int D, float scale, int dtype, unsigned flags, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
+/*
+ * Online-softmax merge of two partial attention results over disjoint key sets
+ * (the rescale of an intermediate result when a further chunk is folded in,
+ * Sec. 4.1): LSE = logaddexp(LSE_a, LSE_b),
+ * O = O_a exp(LSE_a - LSE) + O_b exp(LSE_b - LSE).
+ *   O_a, O_b, O_out [rows,Hq,D] (dtype), LSE_a, LSE_b, LSE_out [Hq,rows] fp32, all
+ *   device; O_out / LSE_out may alias either input.  A partial with LSE = -inf
+ *   (no keys seen) contributes nothing.
+ */
+int fpdt_attn_merge(const void *O_a, const float *LSE_a, const void *O_b, const float *LSE_b,
+                    void *O_out, float *LSE_out, int64_t rows, int Hq, int D, int dtype,
+                    void *stream);
+
+/*
+ * Host-link traffic of the calling thread's most recent fpdt_attn_fwd / fpdt_attn_bwd
+ * call: bytes enqueued host-to-device and device-to-host (0, 0 without offload flags).
+ * Either pointer may be NULL.
+ */
+int fpdt_last_link_bytes(uint64_t *h2d_bytes, uint64_t *d2h_bytes);
+
+/* Text describing the calling thread's most recent error ("" if none). Never NULL. */
+const char *fpdt_last_error(void);
+
+/* Library version string, e.g. "fpdt 0.1 gfx950". */
+const char *fpdt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FPDT_H */

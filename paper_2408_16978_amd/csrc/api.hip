@@ -1,0 +1,761 @@
+// C ABI of libfpdt.so: argument validation, workspace planning and the host-side chunk
+// schedule with its offload pipeline (Sec. 4.1 forward order, Sec. 4.2 backward order and
+// double buffering).  All arithmetic lives in the kernels; this file only decides which
+// chunk pair runs when, where its operands live, and which copies overlap which kernels.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/fpdt.h"
+#include "fpdt_internal.h"
+
+using namespace fpdt;
+
+namespace {
+
+thread_local std::string g_err;
+thread_local uint64_t g_h2d_bytes = 0, g_d2h_bytes = 0;
+
+int fail(int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return fail(FPDT_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_),  \
+                        __FILE__, __LINE__);                                                  \
+    } while (0)
+
+constexpr unsigned KNOWN_FLAGS =
+    FPDT_KV_ON_HOST | FPDT_ACT_ON_HOST | FPDT_BWD_KV_OUTER | FPDT_BWD_Q_OUTER | FPDT_PAIRWISE;
+
+struct Problem {
+    int64_t S, C, u;
+    int Hq, Hkv, D, dtype;
+    unsigned flags;
+    float scale;
+    bool bf16() const { return dtype == FPDT_DTYPE_BF16; }
+    size_t esize() const { return bf16() ? 2 : 4; }
+    bool kv_host() const { return flags & FPDT_KV_ON_HOST; }
+    bool act_host() const { return flags & FPDT_ACT_ON_HOST; }
+    bool fused() const { return bf16() && !(flags & (FPDT_KV_ON_HOST | FPDT_ACT_ON_HOST | FPDT_PAIRWISE)); }
+    bool q_outer() const
+    {
+        if (flags & FPDT_BWD_Q_OUTER) return true;
+        if (flags & FPDT_BWD_KV_OUTER) return false;
+        return act_host();
+    }
+    size_t q_chunk_bytes() const { return (size_t)C * Hq * D * esize(); }
+    size_t kv_chunk_bytes() const { return (size_t)C * Hkv * D * esize(); }
+};
+
+// Scalar validation: touches no GPU.
+int validate_scalars(Problem& p, int64_t S, int64_t chunk, int Hq, int Hkv, int D, float scale,
+                     int dtype, unsigned flags)
+{
+    if (S <= 0 || chunk <= 0) return fail(FPDT_ERR_INVALID_ARG, "S and chunk must be positive (S=%lld chunk=%lld)", (long long)S, (long long)chunk);
+    if (S % chunk != 0) return fail(FPDT_ERR_INVALID_ARG, "S=%lld is not a multiple of chunk=%lld", (long long)S, (long long)chunk);
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return fail(FPDT_ERR_INVALID_ARG, "Hq=%d must be a positive multiple of Hkv=%d", Hq, Hkv);
+    if (!(scale > 0.f) || !std::isfinite(scale)) return fail(FPDT_ERR_INVALID_ARG, "scale must be finite and > 0");
+    if (dtype != FPDT_DTYPE_F32 && dtype != FPDT_DTYPE_BF16) return fail(FPDT_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+    if (flags & ~KNOWN_FLAGS) return fail(FPDT_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags & ~KNOWN_FLAGS);
+    if ((flags & FPDT_BWD_KV_OUTER) && (flags & FPDT_BWD_Q_OUTER)) return fail(FPDT_ERR_INVALID_ARG, "both loop-order flags set");
+    if (D != 64 && D != 80 && D != 128) return fail(FPDT_ERR_UNSUPPORTED, "head dim %d not in {64, 80, 128}", D);
+    if (dtype == FPDT_DTYPE_BF16 && chunk % FPDT_CHUNK_MULTIPLE != 0) return fail(FPDT_ERR_UNSUPPORTED, "bf16 chunk=%lld is not a multiple of %d", (long long)chunk, (int)FPDT_CHUNK_MULTIPLE);
+    if (dtype == FPDT_DTYPE_F32 && (flags & (FPDT_KV_ON_HOST | FPDT_ACT_ON_HOST))) return fail(FPDT_ERR_UNSUPPORTED, "fp32 path has no host offload");
+    if ((flags & FPDT_ACT_ON_HOST) && (flags & FPDT_BWD_KV_OUTER)) return fail(FPDT_ERR_UNSUPPORTED, "FPDT_ACT_ON_HOST needs the Q-outer backward order");
+    if (S > (int64_t)1 << 30 || (int64_t)Hq * (S / 32 + 1) > (int64_t)1 << 30) return fail(FPDT_ERR_UNSUPPORTED, "S=%lld beyond launch limits", (long long)S);
+    p.S = S; p.C = chunk; p.u = S / chunk; p.Hq = Hq; p.Hkv = Hkv; p.D = D; p.dtype = dtype;
+    p.flags = flags; p.scale = scale;
+    return FPDT_OK;
+}
+
+// ---- workspace planning: the same routine sizes (base == nullptr) and carves ----
+struct Bump {
+    char* base;
+    size_t off = 0;
+    explicit Bump(void* b) : base(static_cast<char*>(b)) {}
+    template <typename T = void>
+    T* take(size_t bytes)
+    {
+        off = (off + 255) & ~(size_t)255;
+        T* r = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += bytes;
+        return r;
+    }
+};
+
+struct FwdPlan {
+    void* Knat = nullptr; void* Vtr = nullptr;
+    char* kv_raw[2] = {nullptr, nullptr};
+    float* st_acc = nullptr; float* st_ml = nullptr;
+    char* q_buf[2] = {nullptr, nullptr};
+    char* o_buf[2] = {nullptr, nullptr};
+    float* lse_buf[2] = {nullptr, nullptr};
+    size_t total = 0;
+};
+
+FwdPlan plan_fwd(const Problem& p, void* ws)
+{
+    FwdPlan f;
+    Bump b(ws);
+    if (!p.bf16()) {
+        f.st_acc = b.take<float>((size_t)p.C * p.Hq * p.D * 4);
+        f.st_ml = b.take<float>((size_t)p.C * p.Hq * 2 * 4);
+    } else if (p.fused()) {
+        f.Knat = b.take((size_t)(p.S / 32) * p.Hkv * nat_block_bytes(p.D));
+        f.Vtr = b.take((size_t)(p.S / 32) * p.Hkv * tr_block_bytes(p.D));
+    } else {
+        f.Knat = b.take((size_t)(p.C / 32) * p.Hkv * nat_block_bytes(p.D));
+        f.Vtr = b.take((size_t)(p.C / 32) * p.Hkv * tr_block_bytes(p.D));
+        f.st_acc = b.take<float>(fwd_state_acc_bytes(p.C, p.Hq, p.D));
+        f.st_ml = b.take<float>(fwd_state_ml_bytes(p.C, p.Hq, p.D));
+        if (p.kv_host())
+            for (int i = 0; i < 2; ++i) f.kv_raw[i] = b.take<char>(2 * p.kv_chunk_bytes());
+        if (p.act_host())
+            for (int i = 0; i < 2; ++i) {
+                f.q_buf[i] = b.take<char>(p.q_chunk_bytes());
+                f.o_buf[i] = b.take<char>(p.q_chunk_bytes());
+                f.lse_buf[i] = b.take<float>((size_t)p.Hq * p.C * 4);
+            }
+    }
+    f.total = (b.off + 255) & ~(size_t)255;
+    return f;
+}
+
+struct BwdPlan {
+    float* Delta = nullptr;  // [Hq, S] (resident activations) or 2 x [Hq, C] (streamed)
+    float* delta_buf[2] = {nullptr, nullptr};
+    void *Qnat = nullptr, *Qtr = nullptr, *dOnat = nullptr, *dOtr = nullptr;
+    void *Knat = nullptr, *Vnat = nullptr, *Ktr = nullptr;
+    float *acc_dq = nullptr, *acc_dk = nullptr, *acc_dv = nullptr;
+    char* kv_raw[2] = {nullptr, nullptr};
+    char* dkv_out[2] = {nullptr, nullptr};
+    char* act_raw[2] = {nullptr, nullptr};  // [Q | dO | O] chunk
+    float* lse_buf[2] = {nullptr, nullptr};
+    char* dq_out[2] = {nullptr, nullptr};
+    size_t total = 0;
+};
+
+BwdPlan plan_bwd(const Problem& p, void* ws)
+{
+    BwdPlan f;
+    Bump b(ws);
+    if (!p.bf16()) {
+        f.Delta = b.take<float>((size_t)p.Hq * p.S * 4);
+    } else {
+        const int64_t rows = p.fused() ? p.S : p.C;  // rows covered by the packed buffers
+        f.Qnat = b.take((size_t)(rows / 32) * p.Hq * nat_block_bytes(p.D));
+        f.Qtr = b.take((size_t)(rows / 32) * p.Hq * tr_block_bytes(p.D));
+        f.dOnat = b.take((size_t)(rows / 32) * p.Hq * nat_block_bytes(p.D));
+        f.dOtr = b.take((size_t)(rows / 32) * p.Hq * tr_block_bytes(p.D));
+        f.Knat = b.take((size_t)(rows / 32) * p.Hkv * nat_block_bytes(p.D));
+        f.Vnat = b.take((size_t)(rows / 32) * p.Hkv * nat_block_bytes(p.D));
+        f.Ktr = b.take((size_t)(rows / 32) * p.Hkv * tr_block_bytes(p.D));
+        if (!p.act_host()) f.Delta = b.take<float>((size_t)p.Hq * p.S * 4);
+        if (!p.fused()) {
+            // accumulators: the side that the outer loop holds fixed needs one chunk, the
+            // other side one slot per chunk of the sequence
+            const bool qo = p.q_outer();
+            f.acc_dq = b.take<float>(bwd_acc_dq_bytes(qo ? p.C : p.S, p.Hq, p.D));
+            f.acc_dk = b.take<float>(bwd_acc_dkv_bytes(qo ? p.S : p.C, p.Hkv, p.D));
+            f.acc_dv = b.take<float>(bwd_acc_dkv_bytes(qo ? p.S : p.C, p.Hkv, p.D));
+            if (p.kv_host())
+                for (int i = 0; i < 2; ++i) {
+                    f.kv_raw[i] = b.take<char>(2 * p.kv_chunk_bytes());
+                    f.dkv_out[i] = b.take<char>(2 * p.kv_chunk_bytes());
+                }
+            if (p.act_host())
+                for (int i = 0; i < 2; ++i) {
+                    f.act_raw[i] = b.take<char>(3 * p.q_chunk_bytes());
+                    f.lse_buf[i] = b.take<float>((size_t)p.Hq * p.C * 4);
+                    f.delta_buf[i] = b.take<float>((size_t)p.Hq * p.C * 4);
+                    f.dq_out[i] = b.take<char>(p.q_chunk_bytes());
+                }
+        }
+    }
+    f.total = (b.off + 255) & ~(size_t)255;
+    return f;
+}
+
+// ---- per-device side streams and events for the offload pipeline ----
+enum Ev {
+    EV_FORK, EV_JOIN_H2D, EV_JOIN_D2H,
+    EV_KV_READY0, EV_KV_READY1, EV_KV_FREE0, EV_KV_FREE1,
+    EV_ACT_READY0, EV_ACT_READY1, EV_ACT_FREE0, EV_ACT_FREE1,
+    EV_OUT_DONE0, EV_OUT_DONE1, EV_OUT_COPIED0, EV_OUT_COPIED1,
+    EV_DKV_DONE0, EV_DKV_DONE1, EV_DKV_COPIED0, EV_DKV_COPIED1,
+    EV_COUNT
+};
+
+struct DeviceCtx {
+    bool ready = false;
+    hipStream_t h2d = nullptr, d2h = nullptr;
+    hipEvent_t ev[EV_COUNT] = {};
+};
+std::mutex g_mu;  // serialises enqueueing calls that use the shared side streams
+DeviceCtx g_ctx[64];
+
+int get_ctx(DeviceCtx** out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return fail(FPDT_ERR_HIP, "device index %d out of range", dev);
+    DeviceCtx& c = g_ctx[dev];
+    if (!c.ready) {
+        // default priority on purpose: work on streams of unequal priority is avoided
+        HIP_TRY(hipStreamCreateWithFlags(&c.h2d, hipStreamNonBlocking));
+        HIP_TRY(hipStreamCreateWithFlags(&c.d2h, hipStreamNonBlocking));
+        for (int i = 0; i < EV_COUNT; ++i) HIP_TRY(hipEventCreateWithFlags(&c.ev[i], hipEventDisableTiming));
+        c.ready = true;
+    }
+    *out = &c;
+    return FPDT_OK;
+}
+
+// ---- pointer checks (host side, before any launch) ----
+int check_ptr(const void* ptr, size_t bytes, bool want_host, const char* name)
+{
+    if (!ptr) return fail(FPDT_ERR_INVALID_ARG, "%s is NULL", name);
+    hipPointerAttribute_t at;
+    hipError_t e = hipPointerGetAttributes(&at, ptr);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(FPDT_ERR_INVALID_ARG, "%s is not %s memory known to HIP", name, want_host ? "pinned host" : "device");
+    }
+    if (want_host && at.type != hipMemoryTypeHost) return fail(FPDT_ERR_INVALID_ARG, "%s must be pinned host memory", name);
+    if (!want_host && at.type != hipMemoryTypeDevice) return fail(FPDT_ERR_INVALID_ARG, "%s must be device memory", name);
+    if (!want_host) {
+        void* base = nullptr;
+        size_t size = 0;
+        if (hipMemGetAddressRange((hipDeviceptr_t*)&base, &size, (hipDeviceptr_t)ptr) == hipSuccess) {
+            const char* end = static_cast<const char*>(base) + size;
+            if (static_cast<const char*>(ptr) + bytes > end)
+                return fail(FPDT_ERR_INVALID_ARG, "%s: %zu bytes run past the end of its allocation", name, bytes);
+        } else {
+            (void)hipGetLastError();
+        }
+    }
+    if (reinterpret_cast<uintptr_t>(ptr) % 16 != 0) return fail(FPDT_ERR_INVALID_ARG, "%s must be 16-byte aligned", name);
+    return FPDT_OK;
+}
+
+int check_workspace(void* ws, size_t have, size_t need)
+{
+    if (need == 0) return FPDT_OK;
+    if (!ws) return fail(FPDT_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return fail(FPDT_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (have < need) return fail(FPDT_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", have, need);
+    int rc = check_ptr(ws, need, false, "workspace");
+    if (rc != FPDT_OK) return fail(FPDT_ERR_WORKSPACE, "%s", g_err.c_str());
+    return FPDT_OK;
+}
+
+int launch_status(const char* what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FPDT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return FPDT_OK;
+}
+
+// H2D / D2H helpers that keep the link-byte counters.
+int copy_h2d(void* dst, const void* src, size_t bytes, hipStream_t st)
+{
+    HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st));
+    g_h2d_bytes += bytes;
+    return FPDT_OK;
+}
+int copy_d2h(void* dst, const void* src, size_t bytes, hipStream_t st)
+{
+    HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, st));
+    g_d2h_bytes += bytes;
+    return FPDT_OK;
+}
+
+#define TRY(expr)                       \
+    do {                                \
+        int rc_ = (expr);               \
+        if (rc_ != FPDT_OK) return rc_; \
+    } while (0)
+
+// =========================================================================================
+// forward
+// =========================================================================================
+int fwd_f32(const Problem& p, const float* Q, const float* K, const float* V, float* O, float* LSE,
+            const FwdPlan& f, hipStream_t st)
+{
+    for (int64_t m = 0; m < p.u; ++m)
+        for (int64_t i = 0; i <= m; ++i) {
+            F32FwdArgs a;
+            a.Q = Q + (size_t)m * p.C * p.Hq * p.D;
+            a.K = K + (size_t)i * p.C * p.Hkv * p.D;
+            a.V = V + (size_t)i * p.C * p.Hkv * p.D;
+            a.O = O + (size_t)m * p.C * p.Hq * p.D;
+            a.LSE = LSE + m * p.C;
+            a.lse_stride = p.S;
+            a.st_acc = f.st_acc; a.st_ml = f.st_ml;
+            a.q_pos0 = m * p.C; a.k_pos0 = i * p.C; a.n_q = p.C; a.n_k = p.C;
+            a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
+            a.flags = (i == 0 ? SWEEP_INIT : 0) | (i == m ? SWEEP_FINAL : 0);
+            launch_f32_fwd_pair(a, st);
+        }
+    return launch_status("fp32 forward");
+}
+
+int fwd_bf16_fused(const Problem& p, const void* Q, const void* K, const void* V, void* O, float* LSE,
+                   const FwdPlan& f, hipStream_t st)
+{
+    launch_pack(K, p.S, p.Hkv, p.D, f.Knat, nullptr, p.S / 32, st);
+    launch_pack(V, p.S, p.Hkv, p.D, nullptr, f.Vtr, p.S / 32, st);
+    FwdArgs a;
+    a.Q = Q; a.Knat = f.Knat; a.Vtr = f.Vtr; a.kv_head_stride_blocks = p.S / 32;
+    a.O = O; a.LSE = LSE; a.lse_stride = p.S; a.st_acc = nullptr; a.st_ml = nullptr;
+    a.q_pos0 = 0; a.k_pos0 = 0; a.n_q = p.S; a.n_keys = p.S;
+    a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
+    a.flags = SWEEP_INIT | SWEEP_FINAL;
+    launch_fwd_sweep(a, st);
+    return launch_status("bf16 forward");
+}
+
+// Pair-by-pair forward; K/V chunks (and optionally Q/O/LSE chunks) stream through double
+// buffers on the side streams while the previous pair computes.
+int fwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V, char* O, float* LSE,
+                   const FwdPlan& f, hipStream_t st)
+{
+    const bool kvh = p.kv_host(), acth = p.act_host();
+    DeviceCtx* c = nullptr;
+    if (kvh || acth) {
+        TRY(get_ctx(&c));
+        HIP_TRY(hipEventRecord(c->ev[EV_FORK], st));
+        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_FORK], 0));
+        HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_FORK], 0));
+    }
+    const size_t kvb = p.kv_chunk_bytes(), qb = p.q_chunk_bytes();
+
+    // the K/V fetch sequence is the pair sequence
+    std::vector<int64_t> kv_seq;
+    for (int64_t m = 0; m < p.u; ++m)
+        for (int64_t i = 0; i <= m; ++i) kv_seq.push_back(i);
+    auto fetch_kv = [&](size_t t) -> int {
+        const int b = (int)(t & 1);
+        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_KV_FREE0 + b], 0));
+        TRY(copy_h2d(f.kv_raw[b], K + (size_t)kv_seq[t] * kvb, kvb, c->h2d));
+        TRY(copy_h2d(f.kv_raw[b] + kvb, V + (size_t)kv_seq[t] * kvb, kvb, c->h2d));
+        HIP_TRY(hipEventRecord(c->ev[EV_KV_READY0 + b], c->h2d));
+        return FPDT_OK;
+    };
+    auto fetch_q = [&](int64_t m) -> int {
+        const int b = (int)(m & 1);
+        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_ACT_FREE0 + b], 0));
+        TRY(copy_h2d(f.q_buf[b], Q + (size_t)m * qb, qb, c->h2d));
+        HIP_TRY(hipEventRecord(c->ev[EV_ACT_READY0 + b], c->h2d));
+        return FPDT_OK;
+    };
+
+    if (acth) TRY(fetch_q(0));
+    if (kvh) TRY(fetch_kv(0));
+    size_t t = 0;
+    for (int64_t m = 0; m < p.u; ++m) {
+        const int qbuf = (int)(m & 1);
+        const char* Qm = Q + (size_t)m * qb;
+        char* Om = O + (size_t)m * qb;
+        float* LSEm = LSE + m * p.C;
+        int64_t lse_stride = p.S;
+        if (acth) {
+            if (m + 1 < p.u) TRY(fetch_q(m + 1));
+            HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_ACT_READY0 + qbuf], 0));
+            Qm = f.q_buf[qbuf];
+            Om = f.o_buf[qbuf];
+            LSEm = f.lse_buf[qbuf];
+            lse_stride = p.C;
+        }
+        for (int64_t i = 0; i <= m; ++i, ++t) {
+            const char* Ki = K + (size_t)i * kvb;
+            const char* Vi = V + (size_t)i * kvb;
+            if (kvh) {
+                const int b = (int)(t & 1);
+                if (t + 1 < kv_seq.size()) TRY(fetch_kv(t + 1));
+                HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_KV_READY0 + b], 0));
+                Ki = f.kv_raw[b];
+                Vi = f.kv_raw[b] + kvb;
+            }
+            launch_pack(Ki, p.C, p.Hkv, p.D, f.Knat, nullptr, p.C / 32, st);
+            launch_pack(Vi, p.C, p.Hkv, p.D, nullptr, f.Vtr, p.C / 32, st);
+            if (kvh) HIP_TRY(hipEventRecord(c->ev[EV_KV_FREE0 + (int)(t & 1)], st));
+            if (acth && i == m)  // the finalising sweep overwrites the staging O / LSE chunk
+                HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_OUT_COPIED0 + qbuf], 0));
+            FwdArgs a;
+            a.Q = Qm; a.Knat = f.Knat; a.Vtr = f.Vtr; a.kv_head_stride_blocks = p.C / 32;
+            a.O = Om; a.LSE = LSEm; a.lse_stride = lse_stride;
+            a.st_acc = f.st_acc; a.st_ml = f.st_ml;
+            a.q_pos0 = m * p.C; a.k_pos0 = i * p.C; a.n_q = p.C; a.n_keys = p.C;
+            a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
+            a.flags = (i == 0 ? SWEEP_INIT : 0) | (i == m ? SWEEP_FINAL : 0);
+            launch_fwd_sweep(a, st);
+        }
+        if (acth) {
+            HIP_TRY(hipEventRecord(c->ev[EV_ACT_FREE0 + qbuf], st));
+            HIP_TRY(hipEventRecord(c->ev[EV_OUT_DONE0 + qbuf], st));
+            HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_OUT_DONE0 + qbuf], 0));
+            TRY(copy_d2h(O + (size_t)m * qb, f.o_buf[qbuf], qb, c->d2h));
+            HIP_TRY(hipMemcpy2DAsync(LSE + m * p.C, (size_t)p.S * 4, f.lse_buf[qbuf], (size_t)p.C * 4,
+                                     (size_t)p.C * 4, (size_t)p.Hq, hipMemcpyDeviceToHost, c->d2h));
+            g_d2h_bytes += (size_t)p.C * 4 * p.Hq;
+            HIP_TRY(hipEventRecord(c->ev[EV_OUT_COPIED0 + qbuf], c->d2h));
+        }
+    }
+    if (c) {
+        HIP_TRY(hipEventRecord(c->ev[EV_JOIN_H2D], c->h2d));
+        HIP_TRY(hipEventRecord(c->ev[EV_JOIN_D2H], c->d2h));
+        HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_JOIN_H2D], 0));
+        HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_JOIN_D2H], 0));
+    }
+    return launch_status("bf16 pairwise forward");
+}
+
+// =========================================================================================
+// backward
+// =========================================================================================
+int bwd_f32(const Problem& p, const float* Q, const float* K, const float* V, const float* O,
+            const float* LSE, const float* dO, float* dQ, float* dK, float* dV, const BwdPlan& f,
+            hipStream_t st)
+{
+    launch_zero(dQ, (size_t)p.S * p.Hq * p.D * 4, st);
+    launch_zero(dK, (size_t)p.S * p.Hkv * p.D * 4, st);
+    launch_zero(dV, (size_t)p.S * p.Hkv * p.D * 4, st);
+    launch_delta(O, dO, p.S, p.Hq, p.D, 0, f.Delta, p.S, st);
+    auto pair = [&](int64_t i, int64_t j) {
+        F32BwdArgs a;
+        a.Q = Q + (size_t)i * p.C * p.Hq * p.D;
+        a.dO = dO + (size_t)i * p.C * p.Hq * p.D;
+        a.K = K + (size_t)j * p.C * p.Hkv * p.D;
+        a.V = V + (size_t)j * p.C * p.Hkv * p.D;
+        a.LSE = LSE + i * p.C; a.Delta = f.Delta + i * p.C; a.row_stat_stride = p.S;
+        a.dQ = dQ + (size_t)i * p.C * p.Hq * p.D;
+        a.dK = dK + (size_t)j * p.C * p.Hkv * p.D;
+        a.dV = dV + (size_t)j * p.C * p.Hkv * p.D;
+        a.q_pos0 = i * p.C; a.k_pos0 = j * p.C; a.n_q = p.C; a.n_k = p.C;
+        a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
+        launch_f32_bwd_pair(a, st);
+    };
+    if (p.q_outer()) {
+        for (int64_t i = 0; i < p.u; ++i)
+            for (int64_t j = 0; j <= i; ++j) pair(i, j);
+    } else {
+        for (int64_t j = 0; j < p.u; ++j)
+            for (int64_t i = j; i < p.u; ++i) pair(i, j);
+    }
+    return launch_status("fp32 backward");
+}
+
+int bwd_bf16_fused(const Problem& p, const void* Q, const void* K, const void* V, const void* O,
+                   const float* LSE, const void* dO, void* dQ, void* dK, void* dV, const BwdPlan& f,
+                   hipStream_t st)
+{
+    launch_delta(O, dO, p.S, p.Hq, p.D, 1, f.Delta, p.S, st);
+    launch_pack(Q, p.S, p.Hq, p.D, f.Qnat, f.Qtr, p.S / 32, st);
+    launch_pack(dO, p.S, p.Hq, p.D, f.dOnat, f.dOtr, p.S / 32, st);
+    launch_pack(K, p.S, p.Hkv, p.D, f.Knat, f.Ktr, p.S / 32, st);
+    launch_pack(V, p.S, p.Hkv, p.D, f.Vnat, nullptr, p.S / 32, st);
+    BwdArgs a;
+    a.Q = Q; a.dO = dO; a.K = K; a.V = V;
+    a.Qnat = f.Qnat; a.Qtr = f.Qtr; a.dOnat = f.dOnat; a.dOtr = f.dOtr; a.q_head_stride_blocks = p.S / 32;
+    a.Knat = f.Knat; a.Vnat = f.Vnat; a.Ktr = f.Ktr; a.kv_head_stride_blocks = p.S / 32;
+    a.LSE = LSE; a.Delta = f.Delta; a.row_stat_stride = p.S;
+    a.q_pos0 = 0; a.k_pos0 = 0; a.n_q = p.S; a.n_k = p.S;
+    a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
+    a.acc_dq = nullptr; a.acc_dk = nullptr; a.acc_dv = nullptr;
+    a.dQ = dQ; a.dK = dK; a.dV = dV;
+    a.flags = ACC_FINAL;
+    launch_bwd_dkdv(a, st);
+    launch_bwd_dq(a, st);
+    return launch_status("bf16 backward");
+}
+
+// Pair-by-pair backward in either loop order, with the streamed operands staged through
+// double buffers.  Gradient accumulators stay in fp32 fragment order between pairs: the
+// side held fixed by the outer loop needs one chunk of them, the other side one slot per
+// chunk of the sequence.
+int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V, const char* O,
+                   const float* LSE, const char* dO, char* dQ, char* dK, char* dV, const BwdPlan& f,
+                   hipStream_t st)
+{
+    const bool kvh = p.kv_host(), acth = p.act_host(), qo = p.q_outer();
+    DeviceCtx* c = nullptr;
+    if (kvh || acth) {
+        TRY(get_ctx(&c));
+        HIP_TRY(hipEventRecord(c->ev[EV_FORK], st));
+        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_FORK], 0));
+        HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_FORK], 0));
+    }
+    const size_t kvb = p.kv_chunk_bytes(), qb = p.q_chunk_bytes();
+    const size_t acc_q_chunk = bwd_acc_dq_bytes(p.C, p.Hq, p.D) / 4;     // floats per chunk slot
+    const size_t acc_kv_chunk = bwd_acc_dkv_bytes(p.C, p.Hkv, p.D) / 4;
+
+    if (!acth) launch_delta(O, dO, p.S, p.Hq, p.D, 1, f.Delta, p.S, st);
+
+    // pair order
+    std::vector<std::pair<int64_t, int64_t>> pairs;  // (i = query chunk, j = key chunk)
+    if (qo) {
+        for (int64_t i = 0; i < p.u; ++i)
+            for (int64_t j = 0; j <= i; ++j) pairs.push_back({i, j});
+    } else {
+        for (int64_t j = 0; j < p.u; ++j)
+            for (int64_t i = j; i < p.u; ++i) pairs.push_back({i, j});
+    }
+    // K/V fetch sequence: one fetch whenever the key chunk changes
+    std::vector<int64_t> kv_seq;
+    for (size_t t = 0; t < pairs.size(); ++t)
+        if (t == 0 || pairs[t].second != pairs[t - 1].second) kv_seq.push_back(pairs[t].second);
+
+    auto fetch_kv = [&](size_t n) -> int {
+        const int b = (int)(n & 1);
+        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_KV_FREE0 + b], 0));
+        TRY(copy_h2d(f.kv_raw[b], K + (size_t)kv_seq[n] * kvb, kvb, c->h2d));
+        TRY(copy_h2d(f.kv_raw[b] + kvb, V + (size_t)kv_seq[n] * kvb, kvb, c->h2d));
+        HIP_TRY(hipEventRecord(c->ev[EV_KV_READY0 + b], c->h2d));
+        return FPDT_OK;
+    };
+    // activations (Q-outer only): Q_i, dO_i, O_i and the LSE strip of chunk i
+    auto fetch_act = [&](int64_t i) -> int {
+        const int b = (int)(i & 1);
+        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_ACT_FREE0 + b], 0));
+        TRY(copy_h2d(f.act_raw[b], Q + (size_t)i * qb, qb, c->h2d));
+        TRY(copy_h2d(f.act_raw[b] + qb, dO + (size_t)i * qb, qb, c->h2d));
+        TRY(copy_h2d(f.act_raw[b] + 2 * qb, O + (size_t)i * qb, qb, c->h2d));
+        HIP_TRY(hipMemcpy2DAsync(f.lse_buf[b], (size_t)p.C * 4, LSE + i * p.C, (size_t)p.S * 4,
+                                 (size_t)p.C * 4, (size_t)p.Hq, hipMemcpyHostToDevice, c->h2d));
+        g_h2d_bytes += (size_t)p.C * 4 * p.Hq;
+        HIP_TRY(hipEventRecord(c->ev[EV_ACT_READY0 + b], c->h2d));
+        return FPDT_OK;
+    };
+
+    if (acth) TRY(fetch_act(0));
+    if (kvh) TRY(fetch_kv(0));
+
+    size_t kv_n = 0;         // index into kv_seq of the chunk currently staged
+    int64_t cur_i = -1, cur_j = -1;
+    const char *Qi = nullptr, *dOi = nullptr, *Kj = nullptr, *Vj = nullptr;
+    const float *LSEi = nullptr, *Deltai = nullptr;
+    int64_t stat_stride = p.S;
+    for (size_t t = 0; t < pairs.size(); ++t) {
+        const int64_t i = pairs[t].first, j = pairs[t].second;
+        const bool last_for_q = (j == i);                     // both orders end chunk i's dQ at j == i
+        const bool last_for_kv = (i == p.u - 1);              // and chunk j's dK/dV at i == u-1
+        const bool first_for_q = (j == 0), first_for_kv = (i == j);
+        // ---- key/value side ----
+        if (j != cur_j) {
+            if (kvh) {
+                if (cur_j >= 0) {  // previous staged chunk no longer read by any kernel
+                    HIP_TRY(hipEventRecord(c->ev[EV_KV_FREE0 + (int)(kv_n & 1)], st));
+                    ++kv_n;
+                }
+                if (kv_n + 1 < kv_seq.size()) TRY(fetch_kv(kv_n + 1));
+                const int b = (int)(kv_n & 1);
+                HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_KV_READY0 + b], 0));
+                Kj = f.kv_raw[b];
+                Vj = f.kv_raw[b] + kvb;
+            } else {
+                Kj = K + (size_t)j * kvb;
+                Vj = V + (size_t)j * kvb;
+            }
+            launch_pack(Kj, p.C, p.Hkv, p.D, f.Knat, f.Ktr, p.C / 32, st);
+            launch_pack(Vj, p.C, p.Hkv, p.D, f.Vnat, nullptr, p.C / 32, st);
+            cur_j = j;
+        }
+        // ---- query side ----
+        if (i != cur_i) {
+            if (acth) {
+                if (cur_i >= 0) HIP_TRY(hipEventRecord(c->ev[EV_ACT_FREE0 + (int)(cur_i & 1)], st));
+                if (i + 1 < p.u) TRY(fetch_act(i + 1));
+                const int b = (int)(i & 1);
+                HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_ACT_READY0 + b], 0));
+                Qi = f.act_raw[b];
+                dOi = f.act_raw[b] + qb;
+                launch_delta(f.act_raw[b] + 2 * qb, dOi, p.C, p.Hq, p.D, 1, f.delta_buf[b], p.C, st);
+                LSEi = f.lse_buf[b];
+                Deltai = f.delta_buf[b];
+                stat_stride = p.C;
+            } else {
+                Qi = Q + (size_t)i * qb;
+                dOi = dO + (size_t)i * qb;
+                LSEi = LSE + i * p.C;
+                Deltai = f.Delta + i * p.C;
+                stat_stride = p.S;
+            }
+            launch_pack(Qi, p.C, p.Hq, p.D, f.Qnat, f.Qtr, p.C / 32, st);
+            launch_pack(dOi, p.C, p.Hq, p.D, f.dOnat, f.dOtr, p.C / 32, st);
+            cur_i = i;
+        }
+        // ---- the pair ----
+        BwdArgs a;
+        a.Q = Qi; a.dO = dOi; a.K = Kj; a.V = Vj;
+        a.Qnat = f.Qnat; a.Qtr = f.Qtr; a.dOnat = f.dOnat; a.dOtr = f.dOtr; a.q_head_stride_blocks = p.C / 32;
+        a.Knat = f.Knat; a.Vnat = f.Vnat; a.Ktr = f.Ktr; a.kv_head_stride_blocks = p.C / 32;
+        a.LSE = LSEi; a.Delta = Deltai; a.row_stat_stride = stat_stride;
+        a.q_pos0 = i * p.C; a.k_pos0 = j * p.C; a.n_q = p.C; a.n_k = p.C;
+        a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
+        a.acc_dq = f.acc_dq + (qo ? 0 : (size_t)i * acc_q_chunk);
+        a.acc_dk = f.acc_dk + (qo ? (size_t)j * acc_kv_chunk : 0);
+        a.acc_dv = f.acc_dv + (qo ? (size_t)j * acc_kv_chunk : 0);
+        const int ob_kv = (int)(j & 1), ob_q = (int)(i & 1);
+        a.dK = kvh ? f.dkv_out[ob_kv] : dK + (size_t)j * kvb;
+        a.dV = kvh ? f.dkv_out[ob_kv] + kvb : dV + (size_t)j * kvb;
+        a.dQ = acth ? f.dq_out[ob_q] : dQ + (size_t)i * qb;
+
+        a.flags = (first_for_kv ? 0 : ACC_LOAD) | (last_for_kv ? ACC_FINAL : 0);
+        if (kvh && last_for_kv) HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_DKV_COPIED0 + ob_kv], 0));
+        launch_bwd_dkdv(a, st);
+        if (kvh && last_for_kv) {
+            HIP_TRY(hipEventRecord(c->ev[EV_DKV_DONE0 + ob_kv], st));
+            HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_DKV_DONE0 + ob_kv], 0));
+            TRY(copy_d2h(dK + (size_t)j * kvb, f.dkv_out[ob_kv], kvb, c->d2h));
+            TRY(copy_d2h(dV + (size_t)j * kvb, f.dkv_out[ob_kv] + kvb, kvb, c->d2h));
+            HIP_TRY(hipEventRecord(c->ev[EV_DKV_COPIED0 + ob_kv], c->d2h));
+        }
+
+        a.flags = (first_for_q ? 0 : ACC_LOAD) | (last_for_q ? ACC_FINAL : 0);
+        if (acth && last_for_q) HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_OUT_COPIED0 + ob_q], 0));
+        launch_bwd_dq(a, st);
+        if (acth && last_for_q) {
+            HIP_TRY(hipEventRecord(c->ev[EV_OUT_DONE0 + ob_q], st));
+            HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_OUT_DONE0 + ob_q], 0));
+            TRY(copy_d2h(dQ + (size_t)i * qb, f.dq_out[ob_q], qb, c->d2h));
+            HIP_TRY(hipEventRecord(c->ev[EV_OUT_COPIED0 + ob_q], c->d2h));
+        }
+    }
+    if (c) {
+        HIP_TRY(hipEventRecord(c->ev[EV_JOIN_H2D], c->h2d));
+        HIP_TRY(hipEventRecord(c->ev[EV_JOIN_D2H], c->d2h));
+        HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_JOIN_H2D], 0));
+        HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_JOIN_D2H], 0));
+    }
+    return launch_status("bf16 pairwise backward");
+}
+
+}  // namespace
+
+// =========================================================================================
+// exported entry points
+// =========================================================================================
+extern "C" {
+
+size_t fpdt_attn_workspace_bytes(int64_t S, int64_t chunk, int Hq, int Hkv, int D, int dtype,
+                                 unsigned flags, int is_bwd)
+{
+    Problem p;
+    if (validate_scalars(p, S, chunk, Hq, Hkv, D, 1.f, dtype, flags) != FPDT_OK) return 0;
+    return is_bwd ? plan_bwd(p, nullptr).total : plan_fwd(p, nullptr).total;
+}
+
+int fpdt_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int64_t S,
+                  int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype, unsigned flags,
+                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    g_err.clear();
+    g_h2d_bytes = g_d2h_bytes = 0;
+    if (!Q || !K || !V || !O || !LSE) return fail(FPDT_ERR_INVALID_ARG, "NULL tensor pointer");
+    Problem p;
+    TRY(validate_scalars(p, S, chunk, Hq, Hkv, D, scale, dtype, flags));
+    const size_t need = plan_fwd(p, nullptr).total;
+    if (need && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256))
+        TRY(check_workspace(workspace, workspace_bytes, need));
+    const size_t qbytes = (size_t)S * Hq * D * p.esize(), kbytes = (size_t)S * Hkv * D * p.esize();
+    TRY(check_ptr(Q, qbytes, p.act_host(), "Q"));
+    TRY(check_ptr(K, kbytes, p.kv_host(), "K"));
+    TRY(check_ptr(V, kbytes, p.kv_host(), "V"));
+    TRY(check_ptr(O, qbytes, p.act_host(), "O"));
+    TRY(check_ptr(LSE, (size_t)S * Hq * 4, p.act_host(), "LSE"));
+    TRY(check_workspace(workspace, workspace_bytes, need));
+    const FwdPlan f = plan_fwd(p, workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!p.bf16())
+        return fwd_f32(p, (const float*)Q, (const float*)K, (const float*)V, (float*)O, LSE, f, st);
+    if (p.fused()) return fwd_bf16_fused(p, Q, K, V, O, LSE, f, st);
+    return fwd_bf16_pairs(p, (const char*)Q, (const char*)K, (const char*)V, (char*)O, LSE, f, st);
+}
+
+int fpdt_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                  const void* dO, void* dQ, void* dK, void* dV, int64_t S, int64_t chunk, int Hq,
+                  int Hkv, int D, float scale, int dtype, unsigned flags, void* workspace,
+                  size_t workspace_bytes, void* stream)
+{
+    g_err.clear();
+    g_h2d_bytes = g_d2h_bytes = 0;
+    if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV)
+        return fail(FPDT_ERR_INVALID_ARG, "NULL tensor pointer");
+    Problem p;
+    TRY(validate_scalars(p, S, chunk, Hq, Hkv, D, scale, dtype, flags));
+    const size_t need = plan_bwd(p, nullptr).total;
+    if (need && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256))
+        TRY(check_workspace(workspace, workspace_bytes, need));
+    const size_t qbytes = (size_t)S * Hq * D * p.esize(), kbytes = (size_t)S * Hkv * D * p.esize();
+    TRY(check_ptr(Q, qbytes, p.act_host(), "Q"));
+    TRY(check_ptr(O, qbytes, p.act_host(), "O"));
+    TRY(check_ptr(dO, qbytes, p.act_host(), "dO"));
+    TRY(check_ptr(dQ, qbytes, p.act_host(), "dQ"));
+    TRY(check_ptr(LSE, (size_t)S * Hq * 4, p.act_host(), "LSE"));
+    TRY(check_ptr(K, kbytes, p.kv_host(), "K"));
+    TRY(check_ptr(V, kbytes, p.kv_host(), "V"));
+    TRY(check_ptr(dK, kbytes, p.kv_host(), "dK"));
+    TRY(check_ptr(dV, kbytes, p.kv_host(), "dV"));
+    TRY(check_workspace(workspace, workspace_bytes, need));
+    const BwdPlan f = plan_bwd(p, workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!p.bf16())
+        return bwd_f32(p, (const float*)Q, (const float*)K, (const float*)V, (const float*)O, LSE,
+                       (const float*)dO, (float*)dQ, (float*)dK, (float*)dV, f, st);
+    if (p.fused()) return bwd_bf16_fused(p, Q, K, V, O, LSE, dO, dQ, dK, dV, f, st);
+    return bwd_bf16_pairs(p, (const char*)Q, (const char*)K, (const char*)V, (const char*)O, LSE,
+                          (const char*)dO, (char*)dQ, (char*)dK, (char*)dV, f, st);
+}
+
+int fpdt_attn_merge(const void* O_a, const float* LSE_a, const void* O_b, const float* LSE_b,
+                    void* O_out, float* LSE_out, int64_t rows, int Hq, int D, int dtype, void* stream)
+{
+    g_err.clear();
+    if (!O_a || !LSE_a || !O_b || !LSE_b || !O_out || !LSE_out) return fail(FPDT_ERR_INVALID_ARG, "NULL pointer");
+    if (rows <= 0 || Hq <= 0 || D <= 0) return fail(FPDT_ERR_INVALID_ARG, "rows, Hq and D must be positive");
+    if (dtype != FPDT_DTYPE_F32 && dtype != FPDT_DTYPE_BF16) return fail(FPDT_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+    if (rows * Hq > ((int64_t)1 << 34)) return fail(FPDT_ERR_UNSUPPORTED, "too many rows");
+    const size_t ob = (size_t)rows * Hq * D * (dtype == FPDT_DTYPE_BF16 ? 2 : 4), lb = (size_t)rows * Hq * 4;
+    TRY(check_ptr(O_a, ob, false, "O_a"));
+    TRY(check_ptr(O_b, ob, false, "O_b"));
+    TRY(check_ptr(O_out, ob, false, "O_out"));
+    TRY(check_ptr(LSE_a, lb, false, "LSE_a"));
+    TRY(check_ptr(LSE_b, lb, false, "LSE_b"));
+    TRY(check_ptr(LSE_out, lb, false, "LSE_out"));
+    launch_merge(O_a, LSE_a, O_b, LSE_b, O_out, LSE_out, rows, Hq, D, dtype == FPDT_DTYPE_BF16,
+                 static_cast<hipStream_t>(stream));
+    return launch_status("merge");
+}
+
+int fpdt_last_link_bytes(uint64_t* h2d_bytes, uint64_t* d2h_bytes)
+{
+    if (h2d_bytes) *h2d_bytes = g_h2d_bytes;
+    if (d2h_bytes) *d2h_bytes = g_d2h_bytes;
+    return FPDT_OK;
+}
+
+const char* fpdt_last_error(void) { return g_err.c_str(); }
+
+const char* fpdt_version(void) { return "fpdt 0.1 gfx950"; }
+
+}  // extern "C"

@@ -1,0 +1,473 @@
+// Backward of the chunked attention on bf16 MFMA (Sec. 4.2; operand set of Sec. 3.1).
+//
+//   Delta = rowsum(dO * O)                                   (delta_kernel, HBM-bound)
+//   p  = exp(scale q k^T - LSE), masked above the diagonal
+//   dV += p^T dO,  dP = dO v^T,  dS = p (dP - Delta)
+//   dK += scale dS^T q,  dQ += scale dS k
+//
+// Two MFMA kernels, each keeping its accumulators in registers and recomputing p:
+//   bwd_dkdv_kernel : a workgroup owns 128 keys of one KV head and walks the query rows
+//       (all query heads of the group).  Scores are computed as S = Q K^T (queries are MFMA
+//       rows, keys are columns): a lane owns one key, and the register-resident p and dS
+//       tiles are the B operands of dV^T += dO^T p and dK^T += Q^T dS.
+//   bwd_dq_kernel   : a workgroup owns query rows of one head and walks the keys with
+//       S^T = K Q^T (as in the forward): a lane owns one query, LSE and Delta are per-lane
+//       scalars, and dS^T is the B operand of dQ^T += K^T dS^T.
+// Operands whose contraction runs over rows arrive as TR fragments, the others as NAT
+// fragments (fpdt_internal.h).
+#include "fpdt_internal.h"
+#include "mfma_tiles.h"
+
+namespace fpdt {
+
+namespace {
+
+constexpr int NWAVE = 4;
+constexpr float LOG2E = 1.4426950408889634f;
+
+template <int N>
+__device__ __forceinline__ void seg_gload(u32x4 (&pre)[(N + 255) / 256], const u32x4* src, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < (N + 255) / 256; ++i) {
+        const int idx = tid + 256 * i;
+        if (256 * i + 255 < N || idx < N) pre[i] = src[idx];
+    }
+}
+template <int N>
+__device__ __forceinline__ void seg_sstore(const u32x4 (&pre)[(N + 255) / 256], u32x4* dst, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < (N + 255) / 256; ++i) {
+        const int idx = tid + 256 * i;
+        if (256 * i + 255 < N || idx < N) dst[idx] = pre[i];
+    }
+}
+
+struct BwdKernelArgs {
+    const uint16_t* Q; const uint16_t* dO; const uint16_t* K; const uint16_t* V;
+    const u32x4* Qnat; const u32x4* Qtr; const u32x4* dOnat; const u32x4* dOtr;
+    int64_t q_head_stride_blocks;
+    const u32x4* Knat; const u32x4* Vnat; const u32x4* Ktr;
+    int64_t kv_head_stride_blocks;
+    const float* LSE; const float* Delta; int64_t row_stat_stride;
+    int64_t q_pos0, k_pos0;
+    int n_q, n_k;
+    int Hq, Hkv, g, flags;
+    float scale, c;
+    float* acc_dq; float* acc_dk; float* acc_dv;
+    uint16_t* dQ; uint16_t* dK; uint16_t* dV;
+};
+
+// Store a transposed accumulator tile set (lane = one row `row`, registers = channels) as
+// bf16 into a [rows, H, D] tensor.
+template <int D, int DB>
+__device__ __forceinline__ void store_rows_bf16(const floatx16 (&acc)[DB], float mul, uint16_t* rowp, int half)
+{
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4) {
+            const int d = 32 * db + 8 * a4 + 4 * half;
+            if (d < D) {
+                floatx4 v;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) v[b] = acc[db][4 * a4 + b] * mul;
+                *reinterpret_cast<bf16x4*>(rowp + d) = __builtin_convertvector(v, bf16x4);
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void bwd_dkdv_kernel(BwdKernelArgs p)
+{
+    constexpr int DT = D / 16, DP = (D + 31) / 32 * 32, DB = DP / 32;
+    constexpr int NAT_U4 = DT * 64, TR_U4 = 2 * DB * 64;
+    constexpr int STAGE_U4 = 2 * NAT_U4 + 2 * TR_U4;
+    constexpr int BKT = NWAVE * 32;  // keys per workgroup
+    __shared__ u32x4 smem[2][STAGE_U4];
+    __shared__ float stat[2][64];  // [0,32): LSE*log2e, [32,64): Delta of the staged query block
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const int kvh = blockIdx.x % p.Hkv;
+    const int kt = blockIdx.x / p.Hkv;  // ascending: earliest keys see the most queries, first
+    const int k0 = kt * BKT, kw0 = k0 + 32 * w;
+    const int64_t kpos_w0 = p.k_pos0 + kw0;
+
+    // stationary B operands: lane (key = col, half) holds K/V[key][16t + 8 half + e]
+    bf16x8 kf[DT], vf[DT];
+    {
+        const size_t off = ((size_t)(kw0 + col) * p.Hkv + kvh) * D + 8 * half;
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+            kf[t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.K + off + 16 * t));
+            vf[t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.V + off + 16 * t));
+        }
+    }
+
+    floatx16 dk[DB], dv[DB];
+    const size_t wg = blockIdx.x;
+    float* adk = p.acc_dk + (wg * NWAVE + w) * (size_t)(DB * 16 * 64);
+    float* adv = p.acc_dv + (wg * NWAVE + w) * (size_t)(DB * 16 * 64);
+    if (p.flags & ACC_LOAD) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                dk[db][r] = adk[(db * 16 + r) * 64 + lane];
+                dv[db][r] = adv[(db * 16 + r) * 64 + lane];
+            }
+    } else {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dk[db][r] = dv[db][r] = 0.f;
+    }
+
+    // query blocks (32 rows) that can attend this key tile: position >= first key position
+    const int64_t qmin = p.k_pos0 + k0 - p.q_pos0;
+    const int qb_start = qmin > 0 ? (int)(qmin / 32) : 0;
+    const int n_qb_all = p.n_q / 32;
+    const int n_qb = n_qb_all > qb_start ? n_qb_all - qb_start : 0;
+    const int n_iter = n_qb * p.g;
+
+    u32x4 pre_qn[(NAT_U4 + 255) / 256], pre_on[(NAT_U4 + 255) / 256];
+    u32x4 pre_qt[(TR_U4 + 255) / 256], pre_ot[(TR_U4 + 255) / 256];
+    float pre_stat = 0.f;
+
+#define FPDT_BWD_GLOAD(it_)                                                                     \
+    {                                                                                           \
+        const int hh_ = (it_) / n_qb, qb_ = qb_start + (it_) % n_qb;                            \
+        const int head_ = kvh * p.g + hh_;                                                      \
+        const size_t blk_ = (size_t)head_ * p.q_head_stride_blocks + qb_;                       \
+        seg_gload<NAT_U4>(pre_qn, p.Qnat + blk_ * NAT_U4, tid);                                 \
+        seg_gload<NAT_U4>(pre_on, p.dOnat + blk_ * NAT_U4, tid);                                \
+        seg_gload<TR_U4>(pre_qt, p.Qtr + blk_ * TR_U4, tid);                                    \
+        seg_gload<TR_U4>(pre_ot, p.dOtr + blk_ * TR_U4, tid);                                   \
+        if (tid < 32) pre_stat = p.LSE[(size_t)head_ * p.row_stat_stride + qb_ * 32 + tid] * LOG2E; \
+        else if (tid < 64) pre_stat = p.Delta[(size_t)head_ * p.row_stat_stride + qb_ * 32 + tid - 32]; \
+    }
+#define FPDT_BWD_SSTORE(buf_)                                                  \
+    {                                                                          \
+        seg_sstore<NAT_U4>(pre_qn, smem[buf_], tid);                           \
+        seg_sstore<NAT_U4>(pre_on, smem[buf_] + NAT_U4, tid);                  \
+        seg_sstore<TR_U4>(pre_qt, smem[buf_] + 2 * NAT_U4, tid);               \
+        seg_sstore<TR_U4>(pre_ot, smem[buf_] + 2 * NAT_U4 + TR_U4, tid);       \
+        if (tid < 64) stat[buf_][tid] = pre_stat;                              \
+    }
+
+    if (n_iter > 0) {
+        FPDT_BWD_GLOAD(0);
+        FPDT_BWD_SSTORE(0);
+    }
+    __syncthreads();
+
+    for (int it = 0; it < n_iter; ++it) {
+        const bool more = it + 1 < n_iter;
+        if (more) FPDT_BWD_GLOAD(it + 1);
+        const int buf = it & 1;
+        const u32x4* qn = smem[buf];
+        const u32x4* on = qn + NAT_U4;
+        const u32x4* qt = on + NAT_U4;
+        const u32x4* ot = qt + TR_U4;
+        const int qb = qb_start + it % n_qb;
+        const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
+
+        if (qpos_b0 + 31 >= kpos_w0) {  // wave-uniform: some query of the block reaches this wave's keys
+            floatx16 s, dp;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+#pragma unroll
+            for (int t = 0; t < DT; ++t) s = mfma32(as_bf16x8(qn[t * 64 + lane]), kf[t], s);
+#pragma unroll
+            for (int t = 0; t < DT; ++t) dp = mfma32(as_bf16x8(on[t * 64 + lane]), vf[t], dp);
+            const bool mask = qpos_b0 < kpos_w0 + 31;
+            const int64_t kpos = kpos_w0 + col;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int qr = 8 * (r >> 2) + 4 * half + (r & 3);
+                float e = __builtin_amdgcn_exp2f(fmaf(s[r], p.c, -stat[buf][qr]));
+                if (mask && kpos > qpos_b0 + qr) e = 0.f;
+                const float ds = e * (dp[r] - stat[buf][32 + qr]);
+                s[r] = e;
+                dp[r] = ds;
+            }
+            const bf16x8 pf0 = pack_half<0>(s), pf1 = pack_half<1>(s);
+            const bf16x8 df0 = pack_half<0>(dp), df1 = pack_half<1>(dp);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                dv[db] = mfma32(as_bf16x8(ot[(0 * DB + db) * 64 + lane]), pf0, dv[db]);
+                dv[db] = mfma32(as_bf16x8(ot[(1 * DB + db) * 64 + lane]), pf1, dv[db]);
+                dk[db] = mfma32(as_bf16x8(qt[(0 * DB + db) * 64 + lane]), df0, dk[db]);
+                dk[db] = mfma32(as_bf16x8(qt[(1 * DB + db) * 64 + lane]), df1, dk[db]);
+            }
+        }
+        if (more) FPDT_BWD_SSTORE((it + 1) & 1);
+        __syncthreads();
+    }
+#undef FPDT_BWD_GLOAD
+#undef FPDT_BWD_SSTORE
+
+    if (p.flags & ACC_FINAL) {
+        const size_t off = ((size_t)(kw0 + col) * p.Hkv + kvh) * D;
+        store_rows_bf16<D, DB>(dk, p.scale, p.dK + off, half);
+        store_rows_bf16<D, DB>(dv, 1.f, p.dV + off, half);
+    } else {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                adk[(db * 16 + r) * 64 + lane] = dk[db][r];
+                adv[(db * 16 + r) * 64 + lane] = dv[db][r];
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+template <int D, int NQ>
+__global__ __launch_bounds__(256) void bwd_dq_kernel(BwdKernelArgs p)
+{
+    constexpr int DT = D / 16, DP = (D + 31) / 32 * 32, DB = DP / 32;
+    constexpr int BK = 64, KB = BK / 32;
+    constexpr int BQ = NWAVE * 32 * NQ;
+    constexpr int NAT_U4 = KB * DT * 64, TR_U4 = KB * 2 * DB * 64;  // per tile of BK keys
+    constexpr int STAGE_U4 = 2 * NAT_U4 + TR_U4;
+    __shared__ u32x4 smem[2][STAGE_U4];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const int head = blockIdx.x % p.Hq;
+    const int n_qt = p.n_q / BQ;
+    const int qt = n_qt - 1 - (int)(blockIdx.x / p.Hq);
+    const int kvh = head / p.g;
+    const int q0 = qt * BQ, qw0 = q0 + w * 32 * NQ;
+
+    const int64_t last_q_pos = p.q_pos0 + q0 + BQ - 1;
+    int64_t need = last_q_pos - p.k_pos0 + 1;
+    if (need > p.n_k) need = p.n_k;
+    if (need < 0) need = 0;
+    const int n_tiles = (int)((need + BK - 1) / BK);
+
+    const u32x4* knb = p.Knat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
+    const u32x4* vnb = p.Vnat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
+    const u32x4* ktb = p.Ktr + (size_t)kvh * p.kv_head_stride_blocks * (2 * DB * 64);
+
+    bf16x8 qf[NQ][DT], of[NQ][DT];
+    float lse2[NQ], delta[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        const int row = qw0 + 32 * nq + col;
+        const size_t off = ((size_t)row * p.Hq + head) * D + 8 * half;
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+            qf[nq][t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.Q + off + 16 * t));
+            of[nq][t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.dO + off + 16 * t));
+        }
+        lse2[nq] = p.LSE[(size_t)head * p.row_stat_stride + row] * LOG2E;
+        delta[nq] = p.Delta[(size_t)head * p.row_stat_stride + row];
+    }
+
+    floatx16 acc[NQ][DB];
+    const size_t wg = blockIdx.x;
+    float* aq = p.acc_dq + ((wg * NWAVE + w) * NQ) * (size_t)(DB * 16 * 64);
+    if (p.flags & ACC_LOAD) {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[nq][db][r] = aq[((nq * DB + db) * 16 + r) * 64 + lane];
+    } else {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[nq][db][r] = 0.f;
+    }
+
+    u32x4 pre_k[(NAT_U4 + 255) / 256], pre_v[(NAT_U4 + 255) / 256], pre_t[(TR_U4 + 255) / 256];
+#define FPDT_DQ_GLOAD(it_)                                                \
+    {                                                                     \
+        seg_gload<NAT_U4>(pre_k, knb + (size_t)(it_) * NAT_U4, tid);      \
+        seg_gload<NAT_U4>(pre_v, vnb + (size_t)(it_) * NAT_U4, tid);      \
+        seg_gload<TR_U4>(pre_t, ktb + (size_t)(it_) * TR_U4, tid);        \
+    }
+#define FPDT_DQ_SSTORE(buf_)                                              \
+    {                                                                     \
+        seg_sstore<NAT_U4>(pre_k, smem[buf_], tid);                       \
+        seg_sstore<NAT_U4>(pre_v, smem[buf_] + NAT_U4, tid);              \
+        seg_sstore<TR_U4>(pre_t, smem[buf_] + 2 * NAT_U4, tid);           \
+    }
+    if (n_tiles > 0) {
+        FPDT_DQ_GLOAD(0);
+        FPDT_DQ_SSTORE(0);
+    }
+    __syncthreads();
+
+    const int64_t qpos_w_last = p.q_pos0 + qw0 + 32 * NQ - 1;
+    for (int it = 0; it < n_tiles; ++it) {
+        const bool more = it + 1 < n_tiles;
+        if (more) FPDT_DQ_GLOAD(it + 1);
+        const u32x4* kn = smem[it & 1];
+        const u32x4* vn = kn + NAT_U4;
+        const u32x4* ktr = vn + NAT_U4;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const int64_t key0 = p.k_pos0 + (int64_t)it * BK + 32 * kb;
+            if (key0 <= qpos_w_last) {  // wave-uniform
+                floatx16 s[NQ], dp[NQ];
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[nq][r] = dp[nq][r] = 0.f;
+#pragma unroll
+                for (int t = 0; t < DT; ++t) {
+                    const bf16x8 a = as_bf16x8(kn[(kb * DT + t) * 64 + lane]);
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq) s[nq] = mfma32(a, qf[nq][t], s[nq]);
+                }
+#pragma unroll
+                for (int t = 0; t < DT; ++t) {
+                    const bf16x8 a = as_bf16x8(vn[(kb * DT + t) * 64 + lane]);
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq) dp[nq] = mfma32(a, of[nq][t], dp[nq]);
+                }
+                bf16x8 df[2][NQ];
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) {
+                    const int64_t qpos = p.q_pos0 + qw0 + 32 * nq + col;
+                    const bool mask = key0 + 31 > p.q_pos0 + qw0 + 32 * nq;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float e = __builtin_amdgcn_exp2f(fmaf(s[nq][r], p.c, -lse2[nq]));
+                        if (mask && key0 + 8 * (r >> 2) + 4 * half + (r & 3) > qpos) e = 0.f;
+                        dp[nq][r] = e * (dp[nq][r] - delta[nq]);
+                    }
+                    df[0][nq] = pack_half<0>(dp[nq]);
+                    df[1][nq] = pack_half<1>(dp[nq]);
+                }
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const bf16x8 a = as_bf16x8(ktr[((kb * 2 + s2) * DB + db) * 64 + lane]);
+#pragma unroll
+                        for (int nq = 0; nq < NQ; ++nq) acc[nq][db] = mfma32(a, df[s2][nq], acc[nq][db]);
+                    }
+            }
+        }
+        if (more) FPDT_DQ_SSTORE((it + 1) & 1);
+        __syncthreads();
+    }
+#undef FPDT_DQ_GLOAD
+#undef FPDT_DQ_SSTORE
+
+    if (p.flags & ACC_FINAL) {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            const int row = qw0 + 32 * nq + col;
+            store_rows_bf16<D, DB>(acc[nq], p.scale, p.dQ + ((size_t)row * p.Hq + head) * D, half);
+        }
+    } else {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) aq[((nq * DB + db) * 16 + r) * 64 + lane] = acc[nq][db][r];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Delta[h][row] = sum_d dO * O.  One wave per (row, head) pair group: lanes split channels.
+template <typename T>
+__device__ __forceinline__ float ld(const T* p);
+template <> __device__ __forceinline__ float ld<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float ld<uint16_t>(const uint16_t* p)
+{
+    return __uint_as_float(((unsigned)*p) << 16);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void delta_kernel(const T* __restrict__ O, const T* __restrict__ dO,
+                                                    int64_t rows, int Hq, int D, float* __restrict__ Delta,
+                                                    int64_t stride)
+{
+    // 16 lanes per (row, head): 4 pairs per wave, 16 pairs per workgroup
+    const int tid = threadIdx.x;
+    const int64_t pair = (int64_t)blockIdx.x * 16 + (tid >> 4);
+    const int sub = tid & 15;
+    if (pair >= rows * Hq) return;  // whole 16-lane groups leave together
+    const T* o = O + (size_t)pair * D;
+    const T* g = dO + (size_t)pair * D;
+    float acc = 0.f;
+    for (int d = sub; d < D; d += 16) acc += ld<T>(o + d) * ld<T>(g + d);
+#pragma unroll
+    for (int m = 8; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    if (sub == 0) {
+        const int64_t row = pair / Hq;
+        const int h = (int)(pair % Hq);
+        Delta[(size_t)h * stride + row] = acc;
+    }
+}
+
+}  // namespace
+
+int bwd_k_tile(int D) { (void)D; return NWAVE * 32; }
+int bwd_q_tile(int D) { (void)D; return NWAVE * 32 * 2; }
+size_t bwd_acc_dq_bytes(int64_t n_q, int Hq, int D) { return (size_t)n_q * Hq * dpad(D) * sizeof(float); }
+size_t bwd_acc_dkv_bytes(int64_t n_k, int Hkv, int D) { return (size_t)n_k * Hkv * dpad(D) * sizeof(float); }
+
+static BwdKernelArgs to_kernel_args(const BwdArgs& a)
+{
+    BwdKernelArgs k;
+    k.Q = (const uint16_t*)a.Q; k.dO = (const uint16_t*)a.dO;
+    k.K = (const uint16_t*)a.K; k.V = (const uint16_t*)a.V;
+    k.Qnat = (const u32x4*)a.Qnat; k.Qtr = (const u32x4*)a.Qtr;
+    k.dOnat = (const u32x4*)a.dOnat; k.dOtr = (const u32x4*)a.dOtr;
+    k.q_head_stride_blocks = a.q_head_stride_blocks;
+    k.Knat = (const u32x4*)a.Knat; k.Vnat = (const u32x4*)a.Vnat; k.Ktr = (const u32x4*)a.Ktr;
+    k.kv_head_stride_blocks = a.kv_head_stride_blocks;
+    k.LSE = a.LSE; k.Delta = a.Delta; k.row_stat_stride = a.row_stat_stride;
+    k.q_pos0 = a.q_pos0; k.k_pos0 = a.k_pos0;
+    k.n_q = (int)a.n_q; k.n_k = (int)a.n_k;
+    k.Hq = a.Hq; k.Hkv = a.Hkv; k.g = a.Hq / a.Hkv; k.flags = a.flags;
+    k.scale = a.scale; k.c = a.scale * LOG2E;
+    k.acc_dq = a.acc_dq; k.acc_dk = a.acc_dk; k.acc_dv = a.acc_dv;
+    k.dQ = (uint16_t*)a.dQ; k.dK = (uint16_t*)a.dK; k.dV = (uint16_t*)a.dV;
+    return k;
+}
+
+void launch_bwd_dkdv(const BwdArgs& a, hipStream_t st)
+{
+    const BwdKernelArgs k = to_kernel_args(a);
+    dim3 grid((unsigned)((a.n_k / bwd_k_tile(a.D)) * a.Hkv));
+    if (a.D == 128) bwd_dkdv_kernel<128><<<grid, 256, 0, st>>>(k);
+    else if (a.D == 80) bwd_dkdv_kernel<80><<<grid, 256, 0, st>>>(k);
+    else bwd_dkdv_kernel<64><<<grid, 256, 0, st>>>(k);
+}
+
+void launch_bwd_dq(const BwdArgs& a, hipStream_t st)
+{
+    const BwdKernelArgs k = to_kernel_args(a);
+    dim3 grid((unsigned)((a.n_q / bwd_q_tile(a.D)) * a.Hq));
+    if (a.D == 128) bwd_dq_kernel<128, 2><<<grid, 256, 0, st>>>(k);
+    else if (a.D == 80) bwd_dq_kernel<80, 2><<<grid, 256, 0, st>>>(k);
+    else bwd_dq_kernel<64, 2><<<grid, 256, 0, st>>>(k);
+}
+
+void launch_delta(const void* O, const void* dO, int64_t rows, int Hq, int D, int is_bf16,
+                  float* Delta, int64_t delta_stride, hipStream_t st)
+{
+    const int64_t pairs = rows * Hq;
+    dim3 grid((unsigned)((pairs + 15) / 16));
+    if (is_bf16)
+        delta_kernel<uint16_t><<<grid, 256, 0, st>>>((const uint16_t*)O, (const uint16_t*)dO, rows, Hq, D, Delta, delta_stride);
+    else
+        delta_kernel<float><<<grid, 256, 0, st>>>((const float*)O, (const float*)dO, rows, Hq, D, Delta, delta_stride);
+}
+
+}  // namespace fpdt

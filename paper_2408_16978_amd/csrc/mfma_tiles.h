@@ -1,0 +1,42 @@
+// Device-side helpers for 64-wide wavefronts and v_mfma_f32_32x32x16_bf16 tiles (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fpdt {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// One 32x32x16 bf16 MFMA: acc[32x32] += A[32x16] * B[16x32].
+//   A operand: lane l holds A[l%32][8*(l/32) + e], e = 0..7
+//   B operand: lane l holds B[8*(l/32) + e][l%32]
+//   acc:       lane l, register r holds C[8*(r/4) + 4*(l/32) + r%4][l%32]
+__device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Row (0..31) of accumulator register r for this lane.
+__device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+// Registers [8*s, 8*s+8) of a 32x32 accumulator, rounded to bf16: the B operand of the
+// next MFMA whose contraction runs over the accumulator's rows (TR packing on the A side).
+template <int s>
+__device__ __forceinline__ bf16x8 pack_half(const floatx16& v)
+{
+    floatx8 t;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t[e] = v[8 * s + e];
+    return __builtin_convertvector(t, bf16x8);
+}
+
+__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+
+}  // namespace fpdt

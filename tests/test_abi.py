@@ -1,0 +1,102 @@
+"""CPU-side checks of the C ABI: the library loads, exports everything the header declares,
+and rejects bad arguments with the documented status before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2408_16978_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2408_16978_amd import build
+        build.build()
+    return B.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fpdt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fpdt_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert {"fpdt_attn_fwd", "fpdt_attn_bwd", "fpdt_attn_merge", "fpdt_attn_workspace_bytes",
+            "fpdt_last_error", "fpdt_last_link_bytes", "fpdt_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert "gfx950" in B.fpdt_version()
+
+
+def test_binding_names_match_header():
+    for n in declared_functions():
+        assert callable(getattr(B, n)), n
+
+
+def test_header_constants_match_binding():
+    text = open(os.path.join(ROOT, "include", "fpdt.h")).read()
+    for name in ("FPDT_KV_ON_HOST", "FPDT_ACT_ON_HOST", "FPDT_BWD_KV_OUTER", "FPDT_BWD_Q_OUTER",
+                 "FPDT_PAIRWISE"):
+        m = re.search(name + r"\s*=\s*1u\s*<<\s*(\d+)", text)
+        assert m and getattr(B, name) == 1 << int(m.group(1)), name
+    assert re.search(r"FPDT_CHUNK_MULTIPLE\s*=\s*256", text) and B.FPDT_CHUNK_MULTIPLE == 256
+
+
+def _fwd(lib, S=1024, chunk=256, Hq=2, Hkv=2, D=64, scale=0.125, dtype=B.FPDT_DTYPE_BF16, flags=0,
+         ptr=0x1000, ws=0x100000, ws_bytes=1 << 40):
+    return lib.fpdt_attn_fwd(ptr, ptr, ptr, ptr, ptr, S, chunk, Hq, Hkv, D, scale, dtype, flags, ws,
+                             ws_bytes, None)
+
+
+def test_invalid_arguments_are_rejected_without_a_gpu(lib):
+    assert _fwd(lib, ptr=None) == B.FPDT_ERR_INVALID_ARG
+    assert "NULL" in B.fpdt_last_error()
+    assert _fwd(lib, S=0) == B.FPDT_ERR_INVALID_ARG
+    assert _fwd(lib, chunk=0) == B.FPDT_ERR_INVALID_ARG
+    assert _fwd(lib, S=1000, chunk=256) == B.FPDT_ERR_INVALID_ARG
+    assert _fwd(lib, Hq=3, Hkv=2) == B.FPDT_ERR_INVALID_ARG
+    assert _fwd(lib, scale=0.0) == B.FPDT_ERR_INVALID_ARG
+    assert _fwd(lib, scale=float("nan")) == B.FPDT_ERR_INVALID_ARG
+    assert _fwd(lib, scale=float("inf")) == B.FPDT_ERR_INVALID_ARG
+    assert _fwd(lib, dtype=7) == B.FPDT_ERR_INVALID_ARG
+    assert _fwd(lib, flags=1 << 20) == B.FPDT_ERR_INVALID_ARG
+    assert _fwd(lib, flags=B.FPDT_BWD_KV_OUTER | B.FPDT_BWD_Q_OUTER) == B.FPDT_ERR_INVALID_ARG
+    assert _fwd(lib, D=96) == B.FPDT_ERR_UNSUPPORTED
+    assert _fwd(lib, S=1000, chunk=100) == B.FPDT_ERR_UNSUPPORTED           # bf16 chunk % 256
+    assert _fwd(lib, dtype=B.FPDT_DTYPE_F32, flags=B.FPDT_KV_ON_HOST) == B.FPDT_ERR_UNSUPPORTED
+    assert _fwd(lib, flags=B.FPDT_ACT_ON_HOST | B.FPDT_BWD_KV_OUTER) == B.FPDT_ERR_UNSUPPORTED
+    assert _fwd(lib, ws=None) == B.FPDT_ERR_WORKSPACE
+    assert _fwd(lib, ws_bytes=16) == B.FPDT_ERR_WORKSPACE
+    assert _fwd(lib, ws=0x100010) == B.FPDT_ERR_WORKSPACE                    # misaligned
+    assert B.fpdt_last_error() != ""
+    rc = lib.fpdt_attn_bwd(*([0x1000] * 8), None, 1024, 256, 2, 2, 64, 0.125, 1, 0, 0x100000,
+                           1 << 40, None)
+    assert rc == B.FPDT_ERR_INVALID_ARG
+    rc = lib.fpdt_attn_merge(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0, 2, 64, 1, None)
+    assert rc == B.FPDT_ERR_INVALID_ARG
+
+
+def test_workspace_sizes():
+    ws = B.fpdt_attn_workspace_bytes
+    bf = B.FPDT_DTYPE_BF16
+    assert ws(1000, 256, 2, 2, 64, bf) == 0                                  # invalid -> 0
+    assert ws(1024, 256, 2, 2, 64, B.FPDT_DTYPE_F32) > 0
+    # with K/V offloaded, the forward workspace depends on the chunk, not on S (Sec. 4.1:
+    # only the chunks in use are resident)
+    a = ws(1 << 18, 65536, 8, 2, 128, bf, B.FPDT_KV_ON_HOST)
+    b = ws(1 << 21, 65536, 8, 2, 128, bf, B.FPDT_KV_ON_HOST)
+    assert a == b and a > 0
+    # two raw K/V chunk buffers (2 x 64 MiB) + packed chunk (64 MiB) + carried state
+    assert a < 3 * (1 << 30) // 2
+    # resident mode grows with S
+    assert ws(1 << 21, 65536, 8, 2, 128, bf) > ws(1 << 18, 65536, 8, 2, 128, bf)
+    # backward with everything streamed (Q-outer): only dK/dV accumulators scale with S
+    c = ws(1 << 20, 65536, 8, 1, 128, bf, B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST, True)
+    d = ws(1 << 21, 65536, 8, 1, 128, bf, B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST, True)
+    assert d - c == 2 * (1 << 20) * 1 * 128 * 4

@@ -1,0 +1,142 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element,
+on seeded inputs that span several tiles, several chunks and the diagonal."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2408_16978_amd import binding as B
+from paper_2408_16978_amd import inputs, runner
+from oracle import chunked
+
+import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def run(Q, K, V, dO, chunk, scale, flags=0):
+    b = runner.make_buffers(Q, K, V, dO, chunk, scale, flags)
+    runner.forward(b)
+    runner.backward(b)
+    torch.cuda.synchronize()
+    return {"O": b.O, "LSE": b.LSE, "dQ": b.dQ, "dK": b.dK, "dV": b.dV}
+
+
+def announce(*a):
+    print("[case]", *a, flush=True)
+
+
+def test_tiny_fp32_config():
+    """Config 1: S=1024, 4 chunks of 256, 2 = 2 heads, D=64, fp32; all five outputs."""
+    cfg = inputs.CONFIGS["tiny"]
+    announce(cfg)
+    Q, K, V, dO = inputs.make_qkvdo(cfg.S, cfg.Hq, cfg.Hkv, cfg.D, cfg.dtype, seed=1)
+    ref = parity.oracle_full(Q, K, V, dO, cfg.scale)
+    for flags in (0, B.FPDT_BWD_Q_OUTER):
+        out = run(Q, K, V, dO, cfg.chunk, cfg.scale, flags)
+        print(parity.check_all(out, ref, False))
+
+
+@pytest.mark.parametrize("S,chunk,Hq,Hkv,D", [(300, 100, 4, 2, 80), (768, 256, 8, 1, 128),
+                                              (130, 130, 2, 2, 64), (64, 1, 2, 1, 64)])
+def test_fp32_ragged_shapes(S, chunk, Hq, Hkv, D):
+    announce("fp32", S, chunk, Hq, Hkv, D)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "f32", seed=2)
+    scale = D ** -0.5
+    ref = parity.oracle_full(Q, K, V, dO, scale)
+    out = run(Q, K, V, dO, chunk, scale)
+    print(parity.check_all(out, ref, False))
+
+
+SHAPES = [(2, 2, 64), (4, 4, 80), (8, 2, 128), (8, 1, 128)]
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", SHAPES)
+def test_bf16_resident_full(Hq, Hkv, D):
+    """Everything resident, the chunk pairs walked inside one launch per kernel."""
+    S, chunk = 2048, 256
+    announce("bf16 resident", S, chunk, Hq, Hkv, D)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=3)
+    scale = D ** -0.5
+    ref = parity.oracle_full(Q, K, V, dO, scale)
+    out = run(Q, K, V, dO, chunk, scale)
+    print(parity.check_all(out, ref, True))
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", SHAPES)
+@pytest.mark.parametrize("order", [B.FPDT_BWD_KV_OUTER, B.FPDT_BWD_Q_OUTER])
+def test_bf16_pairwise_full(Hq, Hkv, D, order):
+    """Pair-by-pair schedule with carried fp32 state, 8 chunks, both loop orders."""
+    S, chunk = 2048, 256
+    announce("bf16 pairwise", S, chunk, Hq, Hkv, D, order)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=4)
+    scale = D ** -0.5
+    ref = parity.oracle_full(Q, K, V, dO, scale)
+    out = run(Q, K, V, dO, chunk, scale, B.FPDT_PAIRWISE | order)
+    print(parity.check_all(out, ref, True))
+
+
+@pytest.mark.parametrize("flags", [B.FPDT_KV_ON_HOST | B.FPDT_BWD_KV_OUTER,
+                                   B.FPDT_KV_ON_HOST | B.FPDT_BWD_Q_OUTER,
+                                   B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST])
+def test_offload_is_bitwise_equal_to_pairwise(flags):
+    """Same kernels in the same order: only the copies and events differ, so any difference
+    is a pipeline bug (a missing wait shows as stale or poisoned data)."""
+    S, chunk, Hq, Hkv, D = 4096, 512, 8, 2, 128
+    announce("offload", S, chunk, flags)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=5)
+    scale = D ** -0.5
+    order = B.FPDT_BWD_Q_OUTER if (flags & (B.FPDT_BWD_Q_OUTER | B.FPDT_ACT_ON_HOST)) else B.FPDT_BWD_KV_OUTER
+    base = run(Q, K, V, dO, chunk, scale, B.FPDT_PAIRWISE | order)
+    out = run(Q, K, V, dO, chunk, scale, flags)
+    for n in ("O", "LSE", "dQ", "dK", "dV"):
+        assert torch.equal(out[n].cpu(), base[n].cpu()), n
+    h2d, d2h = B.fpdt_last_link_bytes()
+    assert h2d > 0 and d2h > 0
+    ref = parity.oracle_full(Q, K, V, dO, scale)
+    print(parity.check_all(out, ref, True))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_merge_kernel(dtype):
+    rows, Hq, D = 1000, 4, 80
+    announce("merge", dtype)
+    g = torch.Generator().manual_seed(6)
+    td = inputs.torch_dtype(dtype)
+    Oa = torch.randn(rows, Hq, D, generator=g).to(td)
+    Ob = torch.randn(rows, Hq, D, generator=g).to(td)
+    La = torch.randn(Hq, rows, generator=g) * 3
+    Lb = torch.randn(Hq, rows, generator=g) * 3
+    La[0, :10] = float("-inf")          # partial that saw no keys
+    want_o = np.empty((rows, Hq, D))
+    want_l = np.empty((Hq, rows))
+    for h in range(Hq):
+        with np.errstate(invalid="ignore"):
+            o, l = chunked.merge(parity.to64(Oa)[:, h], La[h].double().numpy(),
+                                 parity.to64(Ob)[:, h], Lb[h].double().numpy())
+        want_o[:, h], want_l[h] = o, l
+    want_o[:10, 0] = parity.to64(Ob)[:10, 0]
+    dev = [t.cuda() for t in (Oa, La, Ob, Lb)]
+    Oo = torch.empty_like(dev[0])
+    Lo = torch.empty_like(dev[1])
+    B.fpdt_attn_merge(dev[0], dev[1], dev[2], dev[3], Oo, Lo)
+    torch.cuda.synchronize()
+    tol = 1e-5 if dtype == "f32" else 2e-2
+    assert np.abs(parity.to64(Oo) - want_o).max() <= tol
+    assert np.abs(Lo.cpu().double().numpy() - want_l).max() <= 1e-5
+
+
+def test_invalid_pointers_are_rejected_on_gpu():
+    """Host pointer where device memory is expected, short workspace: error codes, no launch."""
+    S, chunk, Hq, Hkv, D = 512, 256, 2, 2, 64
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=7)
+    b = runner.make_buffers(Q, K, V, dO, chunk, D ** -0.5)
+    with pytest.raises(B.FpdtError) as e:
+        B.fpdt_attn_fwd(b.Q, K, b.V, b.O, b.LSE, chunk, D ** -0.5, 0, b.ws_fwd)   # K on pageable host
+    assert e.value.status == B.FPDT_ERR_INVALID_ARG
+    with pytest.raises(B.FpdtError) as e:
+        B.fpdt_attn_fwd(b.Q, b.K, b.V, b.O, b.LSE, chunk, D ** -0.5, 0, b.ws_fwd[:1024])
+    assert e.value.status == B.FPDT_ERR_WORKSPACE
+    with pytest.raises(B.FpdtError) as e:   # device K where pinned host memory is required
+        B.fpdt_attn_fwd(b.Q, b.K, b.V, b.O, b.LSE, chunk, D ** -0.5, B.FPDT_KV_ON_HOST,
+                        B.alloc_workspace(S, chunk, Hq, Hkv, D, B.FPDT_DTYPE_BF16, B.FPDT_KV_ON_HOST))
+    assert e.value.status == B.FPDT_ERR_INVALID_ARG
