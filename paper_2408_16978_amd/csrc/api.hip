@@ -468,6 +468,7 @@ int bwd_bf16_fused(const Problem& p, const void* Q, const void* K, const void* V
                    hipStream_t st)
 {
     launch_delta(O, dO, p.S, p.Hq, p.D, 1, f.Delta, p.S, st);
+    launch_delta_head(Q, dO, K, V, LSE, p.S, DELTA_HEAD_ROWS, p.Hq, p.Hkv, p.D, p.scale, f.Delta, st);
     launch_pack(Q, p.S, p.Hq, p.D, f.Qnat, f.Qtr, p.S / 32, st);
     launch_pack(dO, p.S, p.Hq, p.D, f.dOnat, f.dOtr, p.S / 32, st);
     launch_pack(K, p.S, p.Hkv, p.D, f.Knat, f.Ktr, p.S / 32, st);
@@ -602,6 +603,9 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
             launch_pack(dOi, p.C, p.Hq, p.D, f.dOnat, f.dOtr, p.C / 32, st);
             cur_i = i;
         }
+        if (t == 0)  // pair (0, 0): the head of the sequence gets its cancellation-safe Delta
+            launch_delta_head(Qi, dOi, Kj, Vj, LSEi, stat_stride, DELTA_HEAD_ROWS, p.Hq, p.Hkv, p.D,
+                              p.scale, const_cast<float*>(Deltai), st);
         // ---- the pair ----
         BwdArgs a;
         a.Q = Qi; a.dO = dOi; a.K = Kj; a.V = Vj;

@@ -414,6 +414,44 @@ __global__ __launch_bounds__(256) void delta_kernel(const T* __restrict__ O, con
     }
 }
 
+
+// Exact Delta for the first rows of the sequence: Delta_i = sum_j p_ij (dO_i . v_j).
+// rowsum(dO * O) inherits the bf16 rounding of the stored O; for a row with only a few keys
+// the softmax is often peaked, dS = p (dP - Delta) then cancels almost completely and that
+// rounding dominates dQ.  Its weight decays like 1/sqrt(row), so only the head of the
+// sequence is recomputed (plain FMA, one wave per (row, head); the cost is negligible).
+__global__ __launch_bounds__(256) void delta_head_kernel(const uint16_t* __restrict__ Q,
+                                                         const uint16_t* __restrict__ dO,
+                                                         const uint16_t* __restrict__ K,
+                                                         const uint16_t* __restrict__ V,
+                                                         const float* __restrict__ LSE, int64_t stat_stride,
+                                                         int rows, int Hq, int Hkv, int D, float scale,
+                                                         float* __restrict__ Delta)
+{
+    const int lane = threadIdx.x & 63;
+    const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (pair >= rows * Hq) return;  // wave-uniform
+    const int row = pair / Hq, head = pair % Hq;
+    const int kvh = head / (Hq / Hkv);
+    const uint16_t* q = Q + ((size_t)row * Hq + head) * D;
+    const uint16_t* go = dO + ((size_t)row * Hq + head) * D;
+    const float lse = LSE[(size_t)head * stat_stride + row];
+    float acc = 0.f;
+    for (int j = lane; j <= row; j += 64) {
+        const uint16_t* k = K + ((size_t)j * Hkv + kvh) * D;
+        const uint16_t* v = V + ((size_t)j * Hkv + kvh) * D;
+        float s = 0.f, dp = 0.f;
+        for (int d = 0; d < D; ++d) {
+            s = fmaf(ld<uint16_t>(q + d), ld<uint16_t>(k + d), s);
+            dp = fmaf(ld<uint16_t>(go + d), ld<uint16_t>(v + d), dp);
+        }
+        acc = fmaf(expf(scale * s - lse), dp, acc);
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    if (lane == 0) Delta[(size_t)head * stat_stride + row] = acc;
+}
+
 }  // namespace
 
 int bwd_k_tile(int D) { (void)D; return NWAVE * 32; }
@@ -468,6 +506,16 @@ void launch_delta(const void* O, const void* dO, int64_t rows, int Hq, int D, in
         delta_kernel<uint16_t><<<grid, 256, 0, st>>>((const uint16_t*)O, (const uint16_t*)dO, rows, Hq, D, Delta, delta_stride);
     else
         delta_kernel<float><<<grid, 256, 0, st>>>((const float*)O, (const float*)dO, rows, Hq, D, Delta, delta_stride);
+}
+
+void launch_delta_head(const void* Q, const void* dO, const void* K, const void* V, const float* LSE,
+                       int64_t stat_stride, int rows, int Hq, int Hkv, int D, float scale, float* Delta,
+                       hipStream_t st)
+{
+    dim3 grid((unsigned)((rows * Hq + 3) / 4));
+    delta_head_kernel<<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)dO, (const uint16_t*)K,
+                                            (const uint16_t*)V, LSE, stat_stride, rows, Hq, Hkv, D, scale,
+                                            Delta);
 }
 
 }  // namespace fpdt

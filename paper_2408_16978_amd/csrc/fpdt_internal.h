@@ -63,9 +63,16 @@ void launch_fwd_sweep(const FwdArgs& a, hipStream_t st);
 // ---------------------------------------------------------------------------
 // bf16 backward
 // ---------------------------------------------------------------------------
-// Delta[h][row] = sum_d dO[row,h,d] * O[row,h,d]; optionally LSE2 = LSE * log2(e).
+// Delta[h][row] = sum_d dO[row,h,d] * O[row,h,d].
 void launch_delta(const void* O, const void* dO, int64_t rows, int Hq, int D, int is_bf16,
                   float* Delta, int64_t delta_stride, hipStream_t st);
+
+// Overwrite Delta for rows [0, rows) of the sequence with sum_j p_ij (dO_i . v_j), which does
+// not depend on the rounded O.  All pointers are at row 0; rows <= DELTA_HEAD_ROWS.
+enum { DELTA_HEAD_ROWS = 256 };
+void launch_delta_head(const void* Q, const void* dO, const void* K, const void* V, const float* LSE,
+                       int64_t stat_stride, int rows, int Hq, int Hkv, int D, float scale, float* Delta,
+                       hipStream_t st);
 
 enum { ACC_LOAD = 1, ACC_FINAL = 2 };
 
