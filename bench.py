@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the chunked causal attention path (forward + backward) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path -- fpdt_attn_fwd then fpdt_attn_bwd -- over one
+batch of seeded synthetic N(0,1) inputs of the named workload, inputs already resident (in
+HBM, or in pinned host memory for the tensors the workload offloads).  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1)
+    ap.add_argument("--warmup", type=int, default=0)
+    ap.add_argument("--config", default="llama8b_2m")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-link-probe", action="store_true")
+    ap.add_argument("--resident-compare", action="store_true",
+                    help="also time the same pair schedule with K/V resident (exposed copy time)")
+    return ap.parse_args()
+
+
+def link_probe(torch, nbytes):
+    """Bare pinned-memory hipMemcpyAsync rate, GB/s, (h2d, d2h)."""
+    host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    dev = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    out = []
+    for direction in ("h2d", "d2h"):
+        best = 0.0
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            if direction == "h2d":
+                dev.copy_(host, non_blocking=True)
+            else:
+                host.copy_(dev, non_blocking=True)
+            b.record()
+            b.synchronize()
+            best = max(best, nbytes / (a.elapsed_time(b) * 1e-3) / 1e9)
+        out.append(best)
+    return out
+
+
+def cpu_baseline(torch, cfg, K, V, seed):
+    """The fp64 oracle's row evaluator (forward + dQ side of the backward) on a bounded
+    sample of the workload's own rows, timed on the host cores."""
+    import numpy as np
+    from oracle import definition
+    from paper_2408_16978_amd import inputs
+    limit = min(cfg.S, 262144)
+    n_rows = 96
+    rng = np.random.default_rng(1234)
+    rows = np.sort(rng.integers(0, limit, size=n_rows))
+    Kd = K[:limit].to(torch.float64).cpu().numpy()
+    Vd = V[:limit].to(torch.float64).cpu().numpy()
+    Qr = inputs.normal("Q", (n_rows, cfg.Hq, cfg.D), seed + 1, cfg.dtype).to(torch.float64).numpy()
+    dOr = inputs.normal("dO", (n_rows, cfg.Hq, cfg.D), seed + 1, cfg.dtype).to(torch.float64).numpy()
+    t0 = time.perf_counter()
+    definition.rows(Qr, Kd, Vd, rows, cfg.scale, dOr=dOr)
+    dt = time.perf_counter() - t0
+    # scores, PV, dP, dQ: four length-(i+1) passes of 2*D flops per key, per head
+    flops = float(sum(8.0 * cfg.D * (int(i) + 1) for i in rows)) * cfg.Hq
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": definition.threads(),
+            "kind": "oracle",
+            "sample": "row evaluator (O, LSE, Delta, dQ in fp64) on %d random query rows < %d of "
+                      "the workload, all %d heads, %.1f s" % (n_rows, limit, cfg.Hq, dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2408_16978_amd import binding as B, inputs, runner
+
+    cfg = inputs.CONFIGS[args.config]
+    torch.cuda.set_device(0)
+    seed = 2024
+    Q, K, V, dO = inputs.make_qkvdo(cfg.S, cfg.Hq, cfg.Hkv, cfg.D, cfg.dtype, seed, device="cuda")
+    flags = (B.FPDT_KV_ON_HOST if cfg.kv_on_host else 0) | (B.FPDT_ACT_ON_HOST if cfg.act_on_host else 0)
+    bufs = runner.make_buffers(Q, K, V, dO, cfg.chunk, cfg.scale, flags)
+    if cfg.kv_on_host:
+        Kdev, Vdev = K, V
+    del Q, dO
+    torch.cuda.synchronize()
+
+    # code-object load and first-launch costs are paid on a small problem of the same kernels
+    if cfg.dtype == "bf16":
+        w = inputs.make_qkvdo(1024, cfg.Hq, cfg.Hkv, cfg.D, "bf16", 1, device="cuda")
+        wb = runner.make_buffers(*w, 256, cfg.scale, B.FPDT_PAIRWISE)
+        runner.forward(wb)
+        runner.backward(wb)
+        torch.cuda.synchronize()
+        del w, wb
+
+    def step():
+        runner.forward(bufs)
+        runner.backward(bufs)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    B.fpdt_profile_enable(True)
+    fwd_ms = bwd_ms = 0.0
+    link = [0, 0]
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ta = time.perf_counter()
+        runner.forward(bufs)
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        h, d = B.fpdt_last_link_bytes()
+        link[0] += h
+        link[1] += d
+        runner.backward(bufs)
+        torch.cuda.synchronize()
+        tc = time.perf_counter()
+        h, d = B.fpdt_last_link_bytes()
+        link[0] += h
+        link[1] += d
+        fwd_ms += (tb - ta) * 1e3
+        bwd_ms += (tc - tb) * 1e3
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    B.fpdt_profile_enable(False)
+
+    prof = {}
+    for name, kind in (("fwd_sweep", B.FPDT_PROF_FWD), ("bwd_dkdv", B.FPDT_PROF_DKDV),
+                       ("bwd_dq", B.FPDT_PROF_DQ), ("h2d", B.FPDT_PROF_H2D), ("d2h", B.FPDT_PROF_D2H)):
+        ms, n = B.fpdt_profile_read(kind)
+        prof[name] = {"total_ms": ms, "launches": n}
+
+    ms_per_step = total_s * 1e3 / args.steps
+    flops_step = cfg.flops_fwd_bwd()
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+    fwd_flops = cfg.flops_fwd()
+
+    # dominant kernel: the one with the largest summed duration.  Algorithmic FLOPs of a
+    # kernel = 2*D*Hq*S(S+1)/2 per GEMM it is defined by (forward 2, dK/dV 4, dQ 3).
+    gemms = {"fwd_sweep": 2, "bwd_dkdv": 4, "bwd_dq": 3}
+    dom = max(gemms, key=lambda k: prof[k]["total_ms"])
+    per_gemm = 2.0 * cfg.D * cfg.Hq * cfg.S * (cfg.S + 1) / 2.0
+    dom_flops = gemms[dom] * per_gemm * args.steps
+    achieved = dom_flops / (prof[dom]["total_ms"] * 1e-3) / 1e12 if prof[dom]["total_ms"] > 0 else 0.0
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "avg_launch_ms": prof[dom]["total_ms"] / max(1, prof[dom]["launches"]),
+                "launches": prof[dom]["launches"]}
+
+    out = {
+        "metric": "chunked causal attn fwd+bwd TFLOPS",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "S": cfg.S, "chunk": cfg.chunk, "Hq": cfg.Hq, "Hkv": cfg.Hkv,
+                   "D": cfg.D, "kv_on_host": cfg.kv_on_host, "act_on_host": cfg.act_on_host},
+        "frac_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "fwd_ms": fwd_ms / args.steps, "bwd_ms": bwd_ms / args.steps,
+        "fwd_tflops": fwd_flops / (fwd_ms / args.steps * 1e-3) / 1e12,
+        "bwd_tflops": 2.5 * fwd_flops / (bwd_ms / args.steps * 1e-3) / 1e12,
+        "kernels": prof,
+        "roofline": roofline,
+    }
+    if link[0] or link[1]:
+        off = {"h2d_bytes_per_step": link[0] / args.steps, "d2h_bytes_per_step": link[1] / args.steps}
+        if prof["h2d"]["total_ms"] > 0:
+            off["h2d_GBps_while_busy"] = link[0] / (prof["h2d"]["total_ms"] * 1e-3) / 1e9
+        if prof["d2h"]["total_ms"] > 0:
+            off["d2h_GBps_while_busy"] = link[1] / (prof["d2h"]["total_ms"] * 1e-3) / 1e9
+        off["h2d_GBps_needed"] = link[0] / total_s / 1e9
+        out["offload"] = off
+    if not args.no_link_probe:
+        h64, d64 = link_probe(torch, 64 << 20)
+        h1g, d1g = link_probe(torch, 1 << 30)
+        out.setdefault("offload", {})["link_peak_GBps"] = {"h2d_64MiB": h64, "d2h_64MiB": d64,
+                                                          "h2d_1GiB": h1g, "d2h_1GiB": d1g}
+    if args.resident_compare and cfg.kv_on_host and not cfg.act_on_host:
+        # same kernels, same pair order, K/V resident: the difference is the exposed copy time
+        b2 = runner.Buffers(Q=bufs.Q, K=Kdev, V=Vdev, dO=bufs.dO, O=bufs.O, LSE=bufs.LSE, dQ=bufs.dQ,
+                            dK=torch.empty_like(Kdev), dV=torch.empty_like(Vdev),
+                            ws_fwd=B.alloc_workspace(cfg.S, cfg.chunk, cfg.Hq, cfg.Hkv, cfg.D,
+                                                     B.FPDT_DTYPE_BF16, B.FPDT_PAIRWISE, False),
+                            ws_bwd=B.alloc_workspace(cfg.S, cfg.chunk, cfg.Hq, cfg.Hkv, cfg.D,
+                                                     B.FPDT_DTYPE_BF16, B.FPDT_PAIRWISE, True),
+                            chunk=cfg.chunk, scale=cfg.scale, flags=B.FPDT_PAIRWISE)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        runner.forward(b2)
+        runner.backward(b2)
+        torch.cuda.synchronize()
+        res_ms = (time.perf_counter() - t1) * 1e3
+        out["offload"]["resident_pairwise_ms"] = res_ms
+        out["offload"]["exposed_copy_ms"] = ms_per_step - res_ms
+    if not args.no_cpu_baseline:
+        src_k = Kdev if cfg.kv_on_host else bufs.K
+        src_v = Vdev if cfg.kv_on_host else bufs.V
+        out["cpu_baseline"] = cpu_baseline(torch, cfg, src_k, src_v, seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

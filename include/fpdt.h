@@ -140,6 +140,18 @@ int fpdt_attn_merge(const void *O_a, const float *LSE_a, const void *O_b, const 
  */
 int fpdt_last_link_bytes(uint64_t *h2d_bytes, uint64_t *d2h_bytes);
 
+/*
+ * Kernel and copy timing for benchmarks.  While enabled, every launch of the three MFMA
+ * kernels (forward sweep; backward dK/dV; backward dQ) and every host-link copy the
+ * library enqueues is bracketed by HIP events on the stream it runs on.
+ * fpdt_profile_read waits for the recorded events of one kind, returns the summed
+ * duration in milliseconds and the number of launches, and forgets them.
+ */
+enum { FPDT_PROF_FWD = 0, FPDT_PROF_DKDV = 1, FPDT_PROF_DQ = 2, FPDT_PROF_H2D = 3,
+       FPDT_PROF_D2H = 4, FPDT_PROF_KINDS = 5 };
+int fpdt_profile_enable(int on);
+int fpdt_profile_read(int kind, double *total_ms, int64_t *launches);
+
 /* Text describing the calling thread's most recent error ("" if none). Never NULL. */
 const char *fpdt_last_error(void);
 

@@ -21,6 +21,7 @@ FPDT_BWD_KV_OUTER = 1 << 2
 FPDT_BWD_Q_OUTER = 1 << 3
 FPDT_PAIRWISE = 1 << 4
 FPDT_CHUNK_MULTIPLE = 256
+FPDT_PROF_FWD, FPDT_PROF_DKDV, FPDT_PROF_DQ, FPDT_PROF_H2D, FPDT_PROF_D2H = range(5)
 
 _lib = None
 
@@ -52,6 +53,10 @@ def load():
     L.fpdt_attn_merge.argtypes = [vp] * 6 + [i64, ci, ci, ci, vp]
     L.fpdt_last_link_bytes.restype = ci
     L.fpdt_last_link_bytes.argtypes = [ctypes.POINTER(ctypes.c_uint64)] * 2
+    L.fpdt_profile_enable.restype = ci
+    L.fpdt_profile_enable.argtypes = [ci]
+    L.fpdt_profile_read.restype = ci
+    L.fpdt_profile_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     L.fpdt_last_error.restype = ctypes.c_char_p
     L.fpdt_version.restype = ctypes.c_char_p
     _lib = L
@@ -97,6 +102,17 @@ def fpdt_last_link_bytes():
     h, d = ctypes.c_uint64(0), ctypes.c_uint64(0)
     load().fpdt_last_link_bytes(ctypes.byref(h), ctypes.byref(d))
     return int(h.value), int(d.value)
+
+
+def fpdt_profile_enable(on: bool):
+    _check(load().fpdt_profile_enable(int(on)))
+
+
+def fpdt_profile_read(kind: int):
+    """(total milliseconds, launches) of one kind since the last read; waits for the events."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(load().fpdt_profile_read(kind, ctypes.byref(ms), ctypes.byref(n)))
+    return float(ms.value), int(n.value)
 
 
 def fpdt_attn_workspace_bytes(S, chunk, Hq, Hkv, D, dtype, flags=0, is_bwd=False) -> int:

@@ -273,15 +273,44 @@ int launch_status(const char* what)
     return FPDT_OK;
 }
 
+// ---- optional per-kernel timing (benchmarks): HIP events around every launch ----
+struct ProfRec { int kind; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+std::mutex g_prof_mu;
+
+struct ProfScope {
+    hipStream_t st;
+    ProfRec r{};
+    bool live = false;
+    ProfScope(int kind, hipStream_t s) : st(s)
+    {
+        if (!g_prof_on) return;
+        if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+        r.kind = kind;
+        live = hipEventRecord(r.a, st) == hipSuccess;
+    }
+    ~ProfScope()
+    {
+        if (!live) return;
+        (void)hipEventRecord(r.b, st);
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        g_prof.push_back(r);
+    }
+};
+#define PROF(kind, st) ProfScope prof_scope_##__LINE__(kind, st)
+
 // H2D / D2H helpers that keep the link-byte counters.
 int copy_h2d(void* dst, const void* src, size_t bytes, hipStream_t st)
 {
+    PROF(FPDT_PROF_H2D, st);
     HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st));
     g_h2d_bytes += bytes;
     return FPDT_OK;
 }
 int copy_d2h(void* dst, const void* src, size_t bytes, hipStream_t st)
 {
+    PROF(FPDT_PROF_D2H, st);
     HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, st));
     g_d2h_bytes += bytes;
     return FPDT_OK;
@@ -328,7 +357,7 @@ int fwd_bf16_fused(const Problem& p, const void* Q, const void* K, const void* V
     a.q_pos0 = 0; a.k_pos0 = 0; a.n_q = p.S; a.n_keys = p.S;
     a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
     a.flags = SWEEP_INIT | SWEEP_FINAL;
-    launch_fwd_sweep(a, st);
+    { PROF(FPDT_PROF_FWD, st); launch_fwd_sweep(a, st); }
     return launch_status("bf16 forward");
 }
 
@@ -406,7 +435,7 @@ int fwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
             a.q_pos0 = m * p.C; a.k_pos0 = i * p.C; a.n_q = p.C; a.n_keys = p.C;
             a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
             a.flags = (i == 0 ? SWEEP_INIT : 0) | (i == m ? SWEEP_FINAL : 0);
-            launch_fwd_sweep(a, st);
+            { PROF(FPDT_PROF_FWD, st); launch_fwd_sweep(a, st); }
         }
         if (acth) {
             HIP_TRY(hipEventRecord(c->ev[EV_ACT_FREE0 + qbuf], st));
@@ -483,8 +512,8 @@ int bwd_bf16_fused(const Problem& p, const void* Q, const void* K, const void* V
     a.acc_dq = nullptr; a.acc_dk = nullptr; a.acc_dv = nullptr;
     a.dQ = dQ; a.dK = dK; a.dV = dV;
     a.flags = ACC_FINAL;
-    launch_bwd_dkdv(a, st);
-    launch_bwd_dq(a, st);
+    { PROF(FPDT_PROF_DKDV, st); launch_bwd_dkdv(a, st); }
+    { PROF(FPDT_PROF_DQ, st); launch_bwd_dq(a, st); }
     return launch_status("bf16 backward");
 }
 
@@ -624,7 +653,7 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
 
         a.flags = (first_for_kv ? 0 : ACC_LOAD) | (last_for_kv ? ACC_FINAL : 0);
         if (kvh && last_for_kv) HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_DKV_COPIED0 + ob_kv], 0));
-        launch_bwd_dkdv(a, st);
+        { PROF(FPDT_PROF_DKDV, st); launch_bwd_dkdv(a, st); }
         if (kvh && last_for_kv) {
             HIP_TRY(hipEventRecord(c->ev[EV_DKV_DONE0 + ob_kv], st));
             HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_DKV_DONE0 + ob_kv], 0));
@@ -635,7 +664,7 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
 
         a.flags = (first_for_q ? 0 : ACC_LOAD) | (last_for_q ? ACC_FINAL : 0);
         if (acth && last_for_q) HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_OUT_COPIED0 + ob_q], 0));
-        launch_bwd_dq(a, st);
+        { PROF(FPDT_PROF_DQ, st); launch_bwd_dq(a, st); }
         if (acth && last_for_q) {
             HIP_TRY(hipEventRecord(c->ev[EV_OUT_DONE0 + ob_q], st));
             HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_OUT_DONE0 + ob_q], 0));
@@ -755,6 +784,37 @@ int fpdt_last_link_bytes(uint64_t* h2d_bytes, uint64_t* d2h_bytes)
 {
     if (h2d_bytes) *h2d_bytes = g_h2d_bytes;
     if (d2h_bytes) *d2h_bytes = g_d2h_bytes;
+    return FPDT_OK;
+}
+
+int fpdt_profile_enable(int on)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_on = on != 0;
+    return FPDT_OK;
+}
+
+int fpdt_profile_read(int kind, double* total_ms, int64_t* launches)
+{
+    if (kind < 0 || kind >= FPDT_PROF_KINDS) return fail(FPDT_ERR_INVALID_ARG, "unknown profile kind %d", kind);
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    double ms = 0.0;
+    int64_t n = 0;
+    std::vector<ProfRec> keep;
+    for (const ProfRec& r : g_prof) {
+        if (r.kind != kind) { keep.push_back(r); continue; }
+        float t = 0.f;
+        hipError_t e = hipEventSynchronize(r.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, r.a, r.b);
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+        if (e != hipSuccess) { g_prof.swap(keep); return fail(FPDT_ERR_HIP, "profile events: %s", hipGetErrorString(e)); }
+        ms += t;
+        ++n;
+    }
+    g_prof.swap(keep);
+    if (total_ms) *total_ms = ms;
+    if (launches) *launches = n;
     return FPDT_OK;
 }
 
