@@ -65,9 +65,12 @@ def run_config(name, n_random, tail, seed=7):
     want = dO.double().view(cfg.S, cfg.Hkv, g, cfg.D).sum(dim=(0, 2))
     got = dVd.sum(dim=0)
     # rows of p sum to one: sum_j dV_j = sum of dO over the group's heads and all rows.
-    # Each dV element carries an independent bf16 rounding of relative size 2^-9.
-    noise = (dVd.abs() * 2.0 ** -9).pow(2).sum(dim=0).sqrt()
-    assert ((got - want).abs() <= 6 * noise + 1e-3 * want.abs() + 1e-2).all(), "sum dV invariant"
+    # Measured deviation is 2e-5 (S=256K) .. 7e-5 (S=1M) of the norm: bf16 rounding of dV and
+    # the fp32 accumulation of the softmax normaliser over up to S keys.  A dropped or doubled
+    # chunk pair would move it by 1/u or more (>= 3e-2).
+    rel = (got - want).norm() / want.norm()
+    print("sum-dV invariant: relative error", float(rel), flush=True)
+    assert rel < 1e-3, "sum dV invariant"
     # gauge identity: sum_h Q_h^T dQ_h = dK^T K per KV head (D x D); ties the full dK tensor
     # to dQ, which the sampled rows pin.
     Qd, dQd = Q.double(), b.dQ.cuda().double()
