@@ -6,15 +6,17 @@
 //   dK += scale dS^T q,  dQ += scale dS k
 //
 // Two MFMA kernels, each keeping its accumulators in registers and recomputing p:
-//   bwd_dkdv_kernel : a workgroup owns 128 keys of one KV head and walks the query rows
+//   bwd_dkdv_kernel : a workgroup owns 256 keys of one KV head and walks the query rows
 //       (all query heads of the group).  Scores are computed as S = Q K^T (queries are MFMA
 //       rows, keys are columns): a lane owns one key, and the register-resident p and dS
 //       tiles are the B operands of dV^T += dO^T p and dK^T += Q^T dS.
-//   bwd_dq_kernel   : a workgroup owns query rows of one head and walks the keys with
+//   bwd_dq_kernel   : a workgroup owns 256 query rows of one head and walks the keys with
 //       S^T = K Q^T (as in the forward): a lane owns one query, LSE and Delta are per-lane
 //       scalars, and dS^T is the B operand of dQ^T += K^T dS^T.
 // Operands whose contraction runs over rows arrive as TR fragments, the others as NAT
-// fragments (fpdt_internal.h).
+// fragments (fpdt_internal.h).  Both kernels run 8 waves per workgroup (two per SIMD, at
+// most 256 registers each, so one wave's exp / dS arithmetic runs under the other's MFMAs)
+// and stream their operands global -> LDS directly through a small ring.
 #include "fpdt_internal.h"
 #include "mfma_tiles.h"
 
@@ -22,27 +24,9 @@ namespace fpdt {
 
 namespace {
 
-constexpr int NWAVE = 4;
+constexpr int NWAVE = 8;
+constexpr int NTHREAD = NWAVE * 64;
 constexpr float LOG2E = 1.4426950408889634f;
-
-template <int N>
-__device__ __forceinline__ void seg_gload(u32x4 (&pre)[(N + 255) / 256], const u32x4* src, int tid)
-{
-#pragma unroll
-    for (int i = 0; i < (N + 255) / 256; ++i) {
-        const int idx = tid + 256 * i;
-        if (256 * i + 255 < N || idx < N) pre[i] = src[idx];
-    }
-}
-template <int N>
-__device__ __forceinline__ void seg_sstore(const u32x4 (&pre)[(N + 255) / 256], u32x4* dst, int tid)
-{
-#pragma unroll
-    for (int i = 0; i < (N + 255) / 256; ++i) {
-        const int idx = tid + 256 * i;
-        if (256 * i + 255 < N || idx < N) dst[idx] = pre[i];
-    }
-}
 
 struct BwdKernelArgs {
     const uint16_t* Q; const uint16_t* dO; const uint16_t* K; const uint16_t* V;
@@ -59,8 +43,16 @@ struct BwdKernelArgs {
     uint16_t* dQ; uint16_t* dK; uint16_t* dV;
 };
 
-// Store a transposed accumulator tile set (lane = one row `row`, registers = channels) as
-// bf16 into a [rows, H, D] tensor.
+// Direct global -> LDS copy of one 1 KiB fragment by one wave (no VGPR staging): lane l's
+// 16 bytes land at dst + 16 l.
+__device__ __forceinline__ void frag_to_lds(const u32x4* src, u32x4* dst_wave_uniform, int lane)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + lane),
+                                     (__attribute__((address_space(3))) void*)dst_wave_uniform, 16, 0, 0);
+}
+
+// Store a transposed accumulator tile set (lane = one row, registers = channels) as bf16
+// into a [rows, H, D] tensor.
 template <int D, int DB>
 __device__ __forceinline__ void store_rows_bf16(const floatx16 (&acc)[DB], float mul, uint16_t* rowp, int half)
 {
@@ -79,31 +71,40 @@ __device__ __forceinline__ void store_rows_bf16(const floatx16 (&acc)[DB], float
 }
 
 // ---------------------------------------------------------------------------------------
+// dK, dV.  Wave w owns keys [k0 + 32 w, +32): its K fragments are stationary in registers,
+// its V fragments are parked in LDS.  Every step stages one 32-row query block (Q-NAT,
+// dO-NAT, Q-TR, dO-TR, LSE*log2e, Delta) in a 2-slot LDS ring, loaded one step ahead.
 template <int D>
-__global__ __launch_bounds__(256) void bwd_dkdv_kernel(BwdKernelArgs p)
+__global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
 {
     constexpr int DT = D / 16, DP = (D + 31) / 32 * 32, DB = DP / 32;
     constexpr int NAT_U4 = DT * 64, TR_U4 = 2 * DB * 64;
-    constexpr int STAGE_U4 = 2 * NAT_U4 + 2 * TR_U4;
+    constexpr int SLOT_U4 = 2 * NAT_U4 + 2 * TR_U4;
+    constexpr int NFRAG = 2 * DT + 4 * DB;
+    constexpr int RING = 2;
     constexpr int BKT = NWAVE * 32;  // keys per workgroup
-    __shared__ u32x4 smem[2][STAGE_U4];
-    __shared__ float stat[2][64];  // [0,32): LSE*log2e, [32,64): Delta of the staged query block
+    __shared__ u32x4 smem[RING][SLOT_U4];
+    __shared__ u32x4 vst[NWAVE * DT * 64];  // V NAT fragments of the workgroup's keys
+    __shared__ float stat[RING][64];        // [0,32): LSE*log2e, [32,64): Delta of the staged block
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wu = __builtin_amdgcn_readfirstlane(w);
     const int half = lane >> 5, col = lane & 31;
     const int kvh = blockIdx.x % p.Hkv;
     const int kt = blockIdx.x / p.Hkv;  // ascending: earliest keys see the most queries, first
     const int k0 = kt * BKT, kw0 = k0 + 32 * w;
     const int64_t kpos_w0 = p.k_pos0 + kw0;
+    const int64_t kpos = kpos_w0 + col;
 
-    // stationary B operands: lane (key = col, half) holds K/V[key][16t + 8 half + e]
-    bf16x8 kf[DT], vf[DT];
+    bf16x8 kf[DT];
+    u32x4* vmine = vst + wu * (DT * 64);
     {
         const size_t off = ((size_t)(kw0 + col) * p.Hkv + kvh) * D + 8 * half;
+        const u32x4* vsrc = p.Vnat + ((size_t)kvh * p.kv_head_stride_blocks + kw0 / 32) * NAT_U4;
 #pragma unroll
         for (int t = 0; t < DT; ++t) {
             kf[t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.K + off + 16 * t));
-            vf[t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.V + off + 16 * t));
+            frag_to_lds(vsrc + t * 64, vmine + t * 64, lane);
         }
     }
 
@@ -133,82 +134,86 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(BwdKernelArgs p)
     const int n_qb = n_qb_all > qb_start ? n_qb_all - qb_start : 0;
     const int n_iter = n_qb * p.g;
 
-    u32x4 pre_qn[(NAT_U4 + 255) / 256], pre_on[(NAT_U4 + 255) / 256];
-    u32x4 pre_qt[(TR_U4 + 255) / 256], pre_ot[(TR_U4 + 255) / 256];
     float pre_stat = 0.f;
-
-#define FPDT_BWD_GLOAD(it_)                                                                     \
-    {                                                                                           \
-        const int hh_ = (it_) / n_qb, qb_ = qb_start + (it_) % n_qb;                            \
-        const int head_ = kvh * p.g + hh_;                                                      \
-        const size_t blk_ = (size_t)head_ * p.q_head_stride_blocks + qb_;                       \
-        seg_gload<NAT_U4>(pre_qn, p.Qnat + blk_ * NAT_U4, tid);                                 \
-        seg_gload<NAT_U4>(pre_on, p.dOnat + blk_ * NAT_U4, tid);                                \
-        seg_gload<TR_U4>(pre_qt, p.Qtr + blk_ * TR_U4, tid);                                    \
-        seg_gload<TR_U4>(pre_ot, p.dOtr + blk_ * TR_U4, tid);                                   \
-        if (tid < 32) pre_stat = p.LSE[(size_t)head_ * p.row_stat_stride + qb_ * 32 + tid] * LOG2E; \
-        else if (tid < 64) pre_stat = p.Delta[(size_t)head_ * p.row_stat_stride + qb_ * 32 + tid - 32]; \
-    }
-#define FPDT_BWD_SSTORE(buf_)                                                  \
-    {                                                                          \
-        seg_sstore<NAT_U4>(pre_qn, smem[buf_], tid);                           \
-        seg_sstore<NAT_U4>(pre_on, smem[buf_] + NAT_U4, tid);                  \
-        seg_sstore<TR_U4>(pre_qt, smem[buf_] + 2 * NAT_U4, tid);               \
-        seg_sstore<TR_U4>(pre_ot, smem[buf_] + 2 * NAT_U4 + TR_U4, tid);       \
-        if (tid < 64) stat[buf_][tid] = pre_stat;                              \
-    }
+    // Issue the loads of step `it` into ring slot `slot`: wave w copies fragments w, w+8, ...
+    auto issue = [&](int it, int slot) {
+        const int hh = it / n_qb, qb = qb_start + it % n_qb;
+        const int head = kvh * p.g + hh;
+        const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
+#pragma unroll
+        for (int f0 = 0; f0 < NFRAG; f0 += NWAVE) {
+            const int f = f0 + wu;
+            if (f0 + NWAVE <= NFRAG || f < NFRAG) {
+                const u32x4* src = f < DT ? p.Qnat + blk * NAT_U4 + f * 64
+                                 : f < 2 * DT ? p.dOnat + blk * NAT_U4 + (f - DT) * 64
+                                 : f < 2 * DT + 2 * DB ? p.Qtr + blk * TR_U4 + (f - 2 * DT) * 64
+                                                       : p.dOtr + blk * TR_U4 + (f - 2 * DT - 2 * DB) * 64;
+                frag_to_lds(src, &smem[slot][f * 64], lane);
+            }
+        }
+        if (tid < 32) pre_stat = p.LSE[(size_t)head * p.row_stat_stride + qb * 32 + tid] * LOG2E;
+        else if (tid < 64) pre_stat = p.Delta[(size_t)head * p.row_stat_stride + qb * 32 + tid - 32];
+    };
 
     if (n_iter > 0) {
-        FPDT_BWD_GLOAD(0);
-        FPDT_BWD_SSTORE(0);
+        issue(0, 0);
+        if (tid < 64) stat[0][tid] = pre_stat;
     }
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
+    const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int it = 0; it < n_iter; ++it) {
+        const int slot = it % RING, nslot = (it + 1) % RING;
         const bool more = it + 1 < n_iter;
-        if (more) FPDT_BWD_GLOAD(it + 1);
-        const int buf = it & 1;
-        const u32x4* qn = smem[buf];
+        if (more) issue(it + 1, nslot);
+        const u32x4* qn = smem[slot];
         const u32x4* on = qn + NAT_U4;
         const u32x4* qt = on + NAT_U4;
         const u32x4* ot = qt + TR_U4;
+        const float* st = stat[slot];
         const int qb = qb_start + it % n_qb;
         const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
 
         if (qpos_b0 + 31 >= kpos_w0) {  // wave-uniform: some query of the block reaches this wave's keys
+            // S = Q K^T and dP = dO V^T as two interleaved accumulation chains
             floatx16 s, dp;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+            for (int t = 0; t < DT; ++t) {
+                s = mfma32(as_bf16x8(qn[t * 64 + lane]), kf[t], t == 0 ? zero : s);
+                dp = mfma32(as_bf16x8(on[t * 64 + lane]), as_bf16x8(vmine[t * 64 + lane]), t == 0 ? zero : dp);
+            }
+            // p = exp2(s c - lse2), zero above the diagonal
 #pragma unroll
-            for (int t = 0; t < DT; ++t) s = mfma32(as_bf16x8(qn[t * 64 + lane]), kf[t], s);
+            for (int r = 0; r < 16; ++r)
+                s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], p.c, -st[8 * (r >> 2) + 4 * half + (r & 3)]));
+            if (qpos_b0 < kpos_w0 + 31) {  // wave-uniform: the block straddles the diagonal
 #pragma unroll
-            for (int t = 0; t < DT; ++t) dp = mfma32(as_bf16x8(on[t * 64 + lane]), vf[t], dp);
-            const bool mask = qpos_b0 < kpos_w0 + 31;
-            const int64_t kpos = kpos_w0 + col;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int qr = 8 * (r >> 2) + 4 * half + (r & 3);
-                float e = __builtin_amdgcn_exp2f(fmaf(s[r], p.c, -stat[buf][qr]));
-                if (mask && kpos > qpos_b0 + qr) e = 0.f;
-                const float ds = e * (dp[r] - stat[buf][32 + qr]);
-                s[r] = e;
-                dp[r] = ds;
+                for (int r = 0; r < 16; ++r)
+                    if (kpos > qpos_b0 + 8 * (r >> 2) + 4 * half + (r & 3)) s[r] = 0.f;
             }
             const bf16x8 pf0 = pack_half<0>(s), pf1 = pack_half<1>(s);
-            const bf16x8 df0 = pack_half<0>(dp), df1 = pack_half<1>(dp);
+            // dV^T += dO^T p
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
                 dv[db] = mfma32(as_bf16x8(ot[(0 * DB + db) * 64 + lane]), pf0, dv[db]);
                 dv[db] = mfma32(as_bf16x8(ot[(1 * DB + db) * 64 + lane]), pf1, dv[db]);
+            }
+            // dS = p (dP - Delta)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dp[r] = s[r] * (dp[r] - st[32 + 8 * (r >> 2) + 4 * half + (r & 3)]);
+            const bf16x8 df0 = pack_half<0>(dp), df1 = pack_half<1>(dp);
+            // dK^T += Q^T dS
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
                 dk[db] = mfma32(as_bf16x8(qt[(0 * DB + db) * 64 + lane]), df0, dk[db]);
                 dk[db] = mfma32(as_bf16x8(qt[(1 * DB + db) * 64 + lane]), df1, dk[db]);
             }
         }
-        if (more) FPDT_BWD_SSTORE((it + 1) & 1);
+        if (more && tid < 64) stat[nslot][tid] = pre_stat;
+        __builtin_amdgcn_s_waitcnt(0);  // the direct-to-LDS loads of step it+1 have landed
         __syncthreads();
     }
-#undef FPDT_BWD_GLOAD
-#undef FPDT_BWD_SSTORE
 
     if (p.flags & ACC_FINAL) {
         const size_t off = ((size_t)(kw0 + col) * p.Hkv + kvh) * D;
@@ -226,23 +231,29 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(BwdKernelArgs p)
 }
 
 // ---------------------------------------------------------------------------------------
-template <int D, int NQ>
-__global__ __launch_bounds__(256) void bwd_dq_kernel(BwdKernelArgs p)
+// dQ.  Wave w owns query rows [q0 + 32 w, +32) of one head (Q and dO fragments, LSE and Delta
+// stationary in registers).  Every step stages a 64-key tile (K-NAT, V-NAT, K-TR) in a 3-slot
+// LDS ring, loaded two tiles ahead.
+template <int D>
+__global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
 {
     constexpr int DT = D / 16, DP = (D + 31) / 32 * 32, DB = DP / 32;
     constexpr int BK = 64, KB = BK / 32;
-    constexpr int BQ = NWAVE * 32 * NQ;
+    constexpr int BQ = NWAVE * 32;
     constexpr int NAT_U4 = KB * DT * 64, TR_U4 = KB * 2 * DB * 64;  // per tile of BK keys
-    constexpr int STAGE_U4 = 2 * NAT_U4 + TR_U4;
-    __shared__ u32x4 smem[2][STAGE_U4];
+    constexpr int SLOT_U4 = 2 * NAT_U4 + TR_U4;
+    constexpr int NATF = KB * DT, NFRAG = 2 * NATF + KB * 2 * DB;
+    constexpr int RING = 3;
+    __shared__ u32x4 smem[RING][SLOT_U4];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wu = __builtin_amdgcn_readfirstlane(w);
     const int half = lane >> 5, col = lane & 31;
     const int head = blockIdx.x % p.Hq;
     const int n_qt = p.n_q / BQ;
     const int qt = n_qt - 1 - (int)(blockIdx.x / p.Hq);
     const int kvh = head / p.g;
-    const int q0 = qt * BQ, qw0 = q0 + w * 32 * NQ;
+    const int q0 = qt * BQ, qw0 = q0 + w * 32;
 
     const int64_t last_q_pos = p.q_pos0 + q0 + BQ - 1;
     int64_t need = last_q_pos - p.k_pos0 + 1;
@@ -254,130 +265,97 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(BwdKernelArgs p)
     const u32x4* vnb = p.Vnat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
     const u32x4* ktb = p.Ktr + (size_t)kvh * p.kv_head_stride_blocks * (2 * DB * 64);
 
-    bf16x8 qf[NQ][DT], of[NQ][DT];
-    float lse2[NQ], delta[NQ];
+    auto issue = [&](int it, int slot) {
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        const int row = qw0 + 32 * nq + col;
+        for (int f0 = 0; f0 < NFRAG; f0 += NWAVE) {
+            const int f = f0 + wu;
+            if (f0 + NWAVE <= NFRAG || f < NFRAG) {
+                const u32x4* src = f < NATF ? knb + (size_t)it * NAT_U4 + f * 64
+                                 : f < 2 * NATF ? vnb + (size_t)it * NAT_U4 + (f - NATF) * 64
+                                                : ktb + (size_t)it * TR_U4 + (f - 2 * NATF) * 64;
+                frag_to_lds(src, &smem[slot][f * 64], lane);
+            }
+        }
+    };
+
+    bf16x8 qf[DT], of[DT];
+    const int row = qw0 + col;
+    {
         const size_t off = ((size_t)row * p.Hq + head) * D + 8 * half;
 #pragma unroll
         for (int t = 0; t < DT; ++t) {
-            qf[nq][t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.Q + off + 16 * t));
-            of[nq][t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.dO + off + 16 * t));
+            qf[t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.Q + off + 16 * t));
+            of[t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.dO + off + 16 * t));
         }
-        lse2[nq] = p.LSE[(size_t)head * p.row_stat_stride + row] * LOG2E;
-        delta[nq] = p.Delta[(size_t)head * p.row_stat_stride + row];
     }
+    const float lse2 = p.LSE[(size_t)head * p.row_stat_stride + row] * LOG2E;
+    const float delta = p.Delta[(size_t)head * p.row_stat_stride + row];
 
-    floatx16 acc[NQ][DB];
+    floatx16 acc[DB];
     const size_t wg = blockIdx.x;
-    float* aq = p.acc_dq + ((wg * NWAVE + w) * NQ) * (size_t)(DB * 16 * 64);
+    float* aq = p.acc_dq + (wg * NWAVE + w) * (size_t)(DB * 16 * 64);
     if (p.flags & ACC_LOAD) {
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[nq][db][r] = aq[((nq * DB + db) * 16 + r) * 64 + lane];
+            for (int r = 0; r < 16; ++r) acc[db][r] = aq[(db * 16 + r) * 64 + lane];
     } else {
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[nq][db][r] = 0.f;
+            for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
     }
 
-    u32x4 pre_k[(NAT_U4 + 255) / 256], pre_v[(NAT_U4 + 255) / 256], pre_t[(TR_U4 + 255) / 256];
-#define FPDT_DQ_GLOAD(it_)                                                \
-    {                                                                     \
-        seg_gload<NAT_U4>(pre_k, knb + (size_t)(it_) * NAT_U4, tid);      \
-        seg_gload<NAT_U4>(pre_v, vnb + (size_t)(it_) * NAT_U4, tid);      \
-        seg_gload<TR_U4>(pre_t, ktb + (size_t)(it_) * TR_U4, tid);        \
-    }
-#define FPDT_DQ_SSTORE(buf_)                                              \
-    {                                                                     \
-        seg_sstore<NAT_U4>(pre_k, smem[buf_], tid);                       \
-        seg_sstore<NAT_U4>(pre_v, smem[buf_] + NAT_U4, tid);              \
-        seg_sstore<TR_U4>(pre_t, smem[buf_] + 2 * NAT_U4, tid);           \
-    }
-    if (n_tiles > 0) {
-        FPDT_DQ_GLOAD(0);
-        FPDT_DQ_SSTORE(0);
-    }
+    if (n_tiles > 0) issue(0, 0);
+    if (n_tiles > 1) issue(1, 1);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    const int64_t qpos_w_last = p.q_pos0 + qw0 + 32 * NQ - 1;
+    const int64_t qpos_first = p.q_pos0 + qw0, qpos_last = qpos_first + 31, qpos = qpos_first + col;
+    const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int it = 0; it < n_tiles; ++it) {
-        const bool more = it + 1 < n_tiles;
-        if (more) FPDT_DQ_GLOAD(it + 1);
-        const u32x4* kn = smem[it & 1];
+        if (it + 2 < n_tiles) issue(it + 2, (it + 2) % RING);
+        const u32x4* kn = smem[it % RING];
         const u32x4* vn = kn + NAT_U4;
         const u32x4* ktr = vn + NAT_U4;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             const int64_t key0 = p.k_pos0 + (int64_t)it * BK + 32 * kb;
-            if (key0 <= qpos_w_last) {  // wave-uniform
-                floatx16 s[NQ], dp[NQ];
-#pragma unroll
-                for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) s[nq][r] = dp[nq][r] = 0.f;
+            if (key0 <= qpos_last) {  // wave-uniform
+                floatx16 s, dp;
 #pragma unroll
                 for (int t = 0; t < DT; ++t) {
-                    const bf16x8 a = as_bf16x8(kn[(kb * DT + t) * 64 + lane]);
-#pragma unroll
-                    for (int nq = 0; nq < NQ; ++nq) s[nq] = mfma32(a, qf[nq][t], s[nq]);
+                    s = mfma32(as_bf16x8(kn[(kb * DT + t) * 64 + lane]), qf[t], t == 0 ? zero : s);
+                    dp = mfma32(as_bf16x8(vn[(kb * DT + t) * 64 + lane]), of[t], t == 0 ? zero : dp);
                 }
 #pragma unroll
-                for (int t = 0; t < DT; ++t) {
-                    const bf16x8 a = as_bf16x8(vn[(kb * DT + t) * 64 + lane]);
+                for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], p.c, -lse2));
+                if (key0 + 31 > qpos_first) {  // wave-uniform: the block straddles the diagonal
 #pragma unroll
-                    for (int nq = 0; nq < NQ; ++nq) dp[nq] = mfma32(a, of[nq][t], dp[nq]);
-                }
-                bf16x8 df[2][NQ];
-#pragma unroll
-                for (int nq = 0; nq < NQ; ++nq) {
-                    const int64_t qpos = p.q_pos0 + qw0 + 32 * nq + col;
-                    const bool mask = key0 + 31 > p.q_pos0 + qw0 + 32 * nq;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float e = __builtin_amdgcn_exp2f(fmaf(s[nq][r], p.c, -lse2[nq]));
-                        if (mask && key0 + 8 * (r >> 2) + 4 * half + (r & 3) > qpos) e = 0.f;
-                        dp[nq][r] = e * (dp[nq][r] - delta[nq]);
-                    }
-                    df[0][nq] = pack_half<0>(dp[nq]);
-                    df[1][nq] = pack_half<1>(dp[nq]);
+                    for (int r = 0; r < 16; ++r)
+                        if (key0 + 8 * (r >> 2) + 4 * half + (r & 3) > qpos) s[r] = 0.f;
                 }
 #pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2)
+                for (int r = 0; r < 16; ++r) dp[r] = s[r] * (dp[r] - delta);
+                const bf16x8 df0 = pack_half<0>(dp), df1 = pack_half<1>(dp);
 #pragma unroll
-                    for (int db = 0; db < DB; ++db) {
-                        const bf16x8 a = as_bf16x8(ktr[((kb * 2 + s2) * DB + db) * 64 + lane]);
-#pragma unroll
-                        for (int nq = 0; nq < NQ; ++nq) acc[nq][db] = mfma32(a, df[s2][nq], acc[nq][db]);
-                    }
+                for (int db = 0; db < DB; ++db) {
+                    acc[db] = mfma32(as_bf16x8(ktr[((kb * 2 + 0) * DB + db) * 64 + lane]), df0, acc[db]);
+                    acc[db] = mfma32(as_bf16x8(ktr[((kb * 2 + 1) * DB + db) * 64 + lane]), df1, acc[db]);
+                }
             }
         }
-        if (more) FPDT_DQ_SSTORE((it + 1) & 1);
+        __builtin_amdgcn_s_waitcnt(0);  // tiles it+1, it+2 have landed in LDS
         __syncthreads();
     }
-#undef FPDT_DQ_GLOAD
-#undef FPDT_DQ_SSTORE
 
     if (p.flags & ACC_FINAL) {
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            const int row = qw0 + 32 * nq + col;
-            store_rows_bf16<D, DB>(acc[nq], p.scale, p.dQ + ((size_t)row * p.Hq + head) * D, half);
-        }
+        store_rows_bf16<D, DB>(acc, p.scale, p.dQ + ((size_t)row * p.Hq + head) * D, half);
     } else {
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) aq[((nq * DB + db) * 16 + r) * 64 + lane] = acc[nq][db][r];
+            for (int r = 0; r < 16; ++r) aq[(db * 16 + r) * 64 + lane] = acc[db][r];
     }
 }
 
@@ -455,7 +433,7 @@ __global__ __launch_bounds__(256) void delta_head_kernel(const uint16_t* __restr
 }  // namespace
 
 int bwd_k_tile(int D) { (void)D; return NWAVE * 32; }
-int bwd_q_tile(int D) { (void)D; return NWAVE * 32 * 2; }
+int bwd_q_tile(int D) { (void)D; return NWAVE * 32; }
 size_t bwd_acc_dq_bytes(int64_t n_q, int Hq, int D) { return (size_t)n_q * Hq * dpad(D) * sizeof(float); }
 size_t bwd_acc_dkv_bytes(int64_t n_k, int Hkv, int D) { return (size_t)n_k * Hkv * dpad(D) * sizeof(float); }
 
@@ -483,18 +461,18 @@ void launch_bwd_dkdv(const BwdArgs& a, hipStream_t st)
 {
     const BwdKernelArgs k = to_kernel_args(a);
     dim3 grid((unsigned)((a.n_k / bwd_k_tile(a.D)) * a.Hkv));
-    if (a.D == 128) bwd_dkdv_kernel<128><<<grid, 256, 0, st>>>(k);
-    else if (a.D == 80) bwd_dkdv_kernel<80><<<grid, 256, 0, st>>>(k);
-    else bwd_dkdv_kernel<64><<<grid, 256, 0, st>>>(k);
+    if (a.D == 128) bwd_dkdv_kernel<128><<<grid, NTHREAD, 0, st>>>(k);
+    else if (a.D == 80) bwd_dkdv_kernel<80><<<grid, NTHREAD, 0, st>>>(k);
+    else bwd_dkdv_kernel<64><<<grid, NTHREAD, 0, st>>>(k);
 }
 
 void launch_bwd_dq(const BwdArgs& a, hipStream_t st)
 {
     const BwdKernelArgs k = to_kernel_args(a);
     dim3 grid((unsigned)((a.n_q / bwd_q_tile(a.D)) * a.Hq));
-    if (a.D == 128) bwd_dq_kernel<128, 2><<<grid, 256, 0, st>>>(k);
-    else if (a.D == 80) bwd_dq_kernel<80, 2><<<grid, 256, 0, st>>>(k);
-    else bwd_dq_kernel<64, 2><<<grid, 256, 0, st>>>(k);
+    if (a.D == 128) bwd_dq_kernel<128><<<grid, NTHREAD, 0, st>>>(k);
+    else if (a.D == 80) bwd_dq_kernel<80><<<grid, NTHREAD, 0, st>>>(k);
+    else bwd_dq_kernel<64><<<grid, NTHREAD, 0, st>>>(k);
 }
 
 void launch_delta(const void* O, const void* dO, int64_t rows, int Hq, int D, int is_bf16,

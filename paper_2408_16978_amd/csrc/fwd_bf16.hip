@@ -3,13 +3,16 @@
 //
 // Formulation: the score tile is computed transposed, S^T = K Q^T (keys are MFMA rows,
 // queries are MFMA columns).  In the 32x32 accumulator layout a lane then owns ONE query
-// (column lane%32) and 16 keys, so the running max / sum of a query are lane-local up to a
-// single exchange between lanes l and l+32, and the exponentiated tile -- still in
-// registers -- is directly the B operand of O^T += V^T P^T.  K arrives as NAT fragments,
-// V as TR fragments (see fpdt_internal.h); Q is loaded once and stays in registers.
+// (column lane%32) and 16 keys per 32-key block, so the running max of a query needs a single
+// exchange between lanes l and l+32, the running sum none until the epilogue, and the
+// exponentiated tile -- still in registers -- is directly the B operand of O^T += V^T P^T.
+// K arrives as NAT fragments, V as TR fragments (fpdt_internal.h); Q is loaded once and
+// stays in registers.
 //
-// Workgroup = 4 waves; each wave owns NQ blocks of 32 query rows of one head; all waves
-// share the K/V tiles staged (double-buffered) in LDS.
+// Workgroup = 8 waves (two per SIMD, so one wave's softmax arithmetic runs under the other's
+// MFMAs), each wave owns 32 query rows of one head and at most 256 registers; all waves
+// share the 64-key K/V tiles, which travel global -> LDS directly (no register staging)
+// through a 3-slot ring filled two tiles ahead.
 #include "fpdt_internal.h"
 #include "mfma_tiles.h"
 
@@ -17,9 +20,12 @@ namespace fpdt {
 
 namespace {
 
-constexpr int BK = 64;          // keys per LDS tile
-constexpr int KB = BK / 32;     // 32-key blocks per tile
-constexpr int NWAVE = 4;
+constexpr int BK = 64;       // keys per LDS tile
+constexpr int KB = BK / 32;  // 32-key blocks per tile
+constexpr int NWAVE = 8;
+constexpr int NTHREAD = NWAVE * 64;
+constexpr int BQ = NWAVE * 32;  // query rows per workgroup
+constexpr int RING = 3;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -39,235 +45,194 @@ struct FwdKernelArgs {
     float c;  // scale * log2(e)
 };
 
-template <int D, int NQ>
-__global__ __launch_bounds__(256) void fwd_sweep_kernel(FwdKernelArgs p)
+__device__ __forceinline__ void frag_to_lds(const u32x4* src, u32x4* dst_wave_uniform, int lane)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + lane),
+                                     (__attribute__((address_space(3))) void*)dst_wave_uniform, 16, 0, 0);
+}
+
+template <int D>
+__global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
 {
     constexpr int DT = D / 16, DP = (D + 31) / 32 * 32, DB = DP / 32;
-    constexpr int BQ = NWAVE * 32 * NQ;
     constexpr int K_U4 = KB * DT * 64;      // u32x4 per K tile
     constexpr int V_U4 = KB * 2 * DB * 64;  // u32x4 per V tile
     constexpr int T_U4 = K_U4 + V_U4;
-    constexpr int NLD = (T_U4 + 255) / 256;
-    __shared__ u32x4 smem[2][T_U4];
+    constexpr int KFRAG = KB * DT, NFRAG = KFRAG + KB * 2 * DB;  // 1 KiB fragments per tile
+    __shared__ u32x4 smem[RING][T_U4];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wu = __builtin_amdgcn_readfirstlane(w);
     const int half = lane >> 5, col = lane & 31;
     const int head = blockIdx.x % p.Hq;
     const int n_qt = p.n_q / BQ;
     const int qt = n_qt - 1 - (int)(blockIdx.x / p.Hq);  // heaviest (latest) tiles first
     const int kvh = head / p.g;
-    const int q0 = qt * BQ;          // first row of the workgroup within the launch
-    const int qw0 = q0 + w * 32 * NQ;  // first row of this wave
+    const int q0 = qt * BQ;       // first row of the workgroup within the launch
+    const int qw0 = q0 + w * 32;  // first row of this wave
 
     // keys this workgroup needs: positions <= last query position
     const int64_t last_q_pos = p.q_pos0 + q0 + BQ - 1;
     int64_t need = last_q_pos - p.k_pos0 + 1;
     if (need > p.n_keys) need = p.n_keys;
     const int n_tiles = (int)((need + BK - 1) / BK);
-    const bool may_mask = (p.k_pos0 + (int64_t)n_tiles * BK - 1) > (p.q_pos0 + q0);
 
     const u32x4* kbase = p.Knat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
     const u32x4* vbase = p.Vtr + (size_t)kvh * p.kv_head_stride_blocks * (2 * DB * 64);
 
+    // Copy tile `it` into ring slot `slot`: wave w moves fragments w, w+8, ...
+    auto issue = [&](int it, int slot) {
+        const u32x4* ksrc = kbase + (size_t)it * K_U4;
+        const u32x4* vsrc = vbase + (size_t)it * V_U4;
+#pragma unroll
+        for (int f0 = 0; f0 < NFRAG; f0 += NWAVE) {
+            const int f = f0 + wu;
+            if (f0 + NWAVE <= NFRAG || f < NFRAG) {
+                const u32x4* src = f < KFRAG ? ksrc + f * 64 : vsrc + (f - KFRAG) * 64;
+                frag_to_lds(src, &smem[slot][f * 64], lane);
+            }
+        }
+    };
+
     // Q fragments (B operand of S^T = K Q^T): lane (col, half) holds Q[row][16t + 8 half + e]
-    bf16x8 qf[NQ][DT];
+    bf16x8 qf[DT];
+    {
+        const uint16_t* qrow = p.Q + ((size_t)(qw0 + col) * p.Hq + head) * D + 8 * half;
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        const uint16_t* qrow = p.Q + ((size_t)(qw0 + 32 * nq + col) * p.Hq + head) * D + 8 * half;
-#pragma unroll
-        for (int t = 0; t < DT; ++t) qf[nq][t] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 16 * t));
+        for (int t = 0; t < DT; ++t) qf[t] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 16 * t));
     }
 
-    floatx16 acc[NQ][DB];
-    float m_run[NQ], l_run[NQ];  // l_run is this lane's partial sum (its 16 keys per block)
+    floatx16 acc[DB];
+    float m_run, l_run;  // l_run is this lane's partial sum (its 16 keys per block)
     const size_t wg = blockIdx.x;
+    float* sa = p.st_acc + (wg * NWAVE + w) * (size_t)(DB * 16 * 64);
+    float* sm = p.st_ml + (wg * NWAVE + w) * (size_t)(2 * 64);
     if (p.flags & SWEEP_INIT) {
+        m_run = -INFINITY;
+        l_run = 0.f;
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            m_run[nq] = -INFINITY;
-            l_run[nq] = 0.f;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[nq][db][r] = 0.f;
-        }
+            for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
     } else {
-        const float* sa = p.st_acc + ((wg * NWAVE + w) * NQ) * (size_t)(DB * 16 * 64);
-        const float* sm = p.st_ml + ((wg * NWAVE + w) * NQ) * (size_t)(2 * 64);
+        m_run = sm[lane];
+        l_run = sm[64 + lane];
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            m_run[nq] = sm[(nq * 2 + 0) * 64 + lane];
-            l_run[nq] = sm[(nq * 2 + 1) * 64 + lane];
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    acc[nq][db][r] = sa[((nq * DB + db) * 16 + r) * 64 + lane];
-        }
+            for (int r = 0; r < 16; ++r) acc[db][r] = sa[(db * 16 + r) * 64 + lane];
     }
 
-    // ---- tile pipeline: global -> registers -> LDS, one barrier per tile ----
-    u32x4 pre[NLD];
-#define FPDT_GLOAD(it_)                                                            \
-    {                                                                              \
-        const u32x4* ksrc = kbase + (size_t)(it_) * K_U4;                          \
-        const u32x4* vsrc = vbase + (size_t)(it_) * V_U4;                          \
-        _Pragma("unroll") for (int i = 0; i < NLD; ++i)                            \
-        {                                                                          \
-            const int idx = tid + 256 * i;                                         \
-            if (256 * i + 255 < K_U4) pre[i] = ksrc[idx];                          \
-            else if (256 * i >= K_U4 && 256 * i + 255 < T_U4) pre[i] = vsrc[idx - K_U4]; \
-            else if (idx < T_U4) pre[i] = (idx < K_U4) ? ksrc[idx] : vsrc[idx - K_U4];   \
-        }                                                                          \
-    }
-#define FPDT_SSTORE(buf_)                                                          \
-    {                                                                              \
-        _Pragma("unroll") for (int i = 0; i < NLD; ++i)                            \
-        {                                                                          \
-            const int idx = tid + 256 * i;                                         \
-            if (256 * i + 255 < T_U4 || idx < T_U4) smem[buf_][idx] = pre[i];      \
-        }                                                                          \
-    }
-
-    if (n_tiles > 0) {
-        FPDT_GLOAD(0);
-        FPDT_SSTORE(0);
-    }
+    if (n_tiles > 0) issue(0, 0);
+    if (n_tiles > 1) issue(1, 1);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    const int64_t qpos_w_last = p.q_pos0 + qw0 + 32 * NQ - 1;  // last query position of this wave
+    const int64_t qpos_first = p.q_pos0 + qw0;  // first / last query position of this wave
+    const int64_t qpos_last = qpos_first + 31;
+    const int64_t qpos = qpos_first + col;
+    const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     for (int it = 0; it < n_tiles; ++it) {
-        const bool more = (it + 1 < n_tiles);
-        if (more) FPDT_GLOAD(it + 1);
-        const u32x4* ks = smem[it & 1];
+        if (it + 2 < n_tiles) issue(it + 2, (it + 2) % RING);
+        const u32x4* ks = smem[it % RING];
         const u32x4* vs = ks + K_U4;
         const int64_t key0 = p.k_pos0 + (int64_t)it * BK;  // position of the tile's first key
 
-        if (key0 <= qpos_w_last) {  // wave-uniform: tile not entirely above this wave's diagonal
+        if (key0 <= qpos_last) {  // wave-uniform: tile not entirely above this wave's diagonal
             // ---- S^T = K Q^T for the whole tile ----
-            floatx16 s[KB][NQ];
+            floatx16 s[KB];
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
+            for (int t = 0; t < DT; ++t)
 #pragma unroll
-                for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) s[kb][nq][r] = 0.f;
-#pragma unroll
-                for (int t = 0; t < DT; ++t) {
-                    const bf16x8 a = as_bf16x8(ks[(kb * DT + t) * 64 + lane]);
-#pragma unroll
-                    for (int nq = 0; nq < NQ; ++nq) s[kb][nq] = mfma32(a, qf[nq][t], s[kb][nq]);
-                }
-            }
+                for (int kb = 0; kb < KB; ++kb)
+                    s[kb] = mfma32(as_bf16x8(ks[(kb * DT + t) * 64 + lane]), qf[t], t == 0 ? zero : s[kb]);
             // ---- online softmax, one query per lane ----
-            bf16x8 pf[KB][2][NQ];
-#pragma unroll
-            for (int nq = 0; nq < NQ; ++nq) {
-                const int64_t qpos = p.q_pos0 + qw0 + 32 * nq + col;
-                if (may_mask && key0 + BK - 1 > p.q_pos0 + qw0 + 32 * nq) {  // wave-uniform
-#pragma unroll
-                    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int64_t kpos = key0 + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
-                            if (kpos > qpos) s[kb][nq][r] = -INFINITY;
-                        }
-                }
-                float mx = s[0][nq][0];
+            if (key0 + BK - 1 > qpos_first) {  // wave-uniform: the tile straddles the diagonal
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][nq][r]);
-                mx = fmaxf(mx, xor32(mx));
-                const float m_new = fmaxf(m_run[nq], mx * p.c);
-                // Rescale only when some query of the wave raised its maximum.
-                if (__any(m_new != m_run[nq])) {
-                    const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
-                    l_run[nq] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) acc[nq][db][r] *= alpha;
-                    m_run[nq] = m_new;
-                }
-                float lsum = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const float e = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][r], p.c, -m_new));
-                        s[kb][nq][r] = e;
-                        lsum += e;
+                        const int64_t kpos = key0 + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
+                        if (kpos > qpos) s[kb][r] = -INFINITY;
                     }
-                    pf[kb][0][nq] = pack_half<0>(s[kb][nq]);
-                    pf[kb][1][nq] = pack_half<1>(s[kb][nq]);
-                }
-                l_run[nq] += lsum;
             }
+            float mx = fmaxf(s[0][0], s[0][1]);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int r = (kb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[kb][r]), s[kb][r + 1]);
+            mx = fmaxf(mx, xor32(mx));
+            const float m_new = fmaxf(m_run, mx * p.c);
+            // Rescale only when some query of the wave raised its maximum.
+            if (__any(m_new != m_run)) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[db][r] *= alpha;
+                m_run = m_new;
+            }
+            bf16x8 pf[KB][2];
+            float lsum = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float e = __builtin_amdgcn_exp2f(fmaf(s[kb][r], p.c, -m_new));
+                    s[kb][r] = e;
+                    lsum += e;
+                }
+                pf[kb][0] = pack_half<0>(s[kb]);
+                pf[kb][1] = pack_half<1>(s[kb]);
+            }
+            l_run += lsum;
             // ---- O^T += V^T P^T ----
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-                    for (int db = 0; db < DB; ++db) {
-                        const bf16x8 a = as_bf16x8(vs[((kb * 2 + s2) * DB + db) * 64 + lane]);
-#pragma unroll
-                        for (int nq = 0; nq < NQ; ++nq)
-                            acc[nq][db] = mfma32(a, pf[kb][s2][nq], acc[nq][db]);
-                    }
+                    for (int db = 0; db < DB; ++db)
+                        acc[db] = mfma32(as_bf16x8(vs[((kb * 2 + s2) * DB + db) * 64 + lane]), pf[kb][s2], acc[db]);
         }
-        if (more) FPDT_SSTORE((it + 1) & 1);
+        __builtin_amdgcn_s_waitcnt(0);  // tiles it+1, it+2 have landed in LDS
         __syncthreads();
     }
 
     // ---- epilogue ----
     if (p.flags & SWEEP_FINAL) {
+        const float l_tot = l_run + xor32(l_run);
+        const float inv = 1.f / l_tot;
+        const int row = qw0 + col;
+        uint16_t* orow = p.O + ((size_t)row * p.Hq + head) * D;
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            const float l_tot = l_run[nq] + xor32(l_run[nq]);
-            const float inv = 1.f / l_tot;
-            const int row = qw0 + 32 * nq + col;
-            uint16_t* orow = p.O + ((size_t)row * p.Hq + head) * D;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+            for (int a4 = 0; a4 < 4; ++a4) {
+                const int d = 32 * db + 8 * a4 + 4 * half;
+                if (d < D) {
+                    floatx4 v;
 #pragma unroll
-                for (int a4 = 0; a4 < 4; ++a4) {
-                    const int d = 32 * db + 8 * a4 + 4 * half;
-                    if (d < D) {
-                        floatx4 v;
-#pragma unroll
-                        for (int b = 0; b < 4; ++b) v[b] = acc[nq][db][4 * a4 + b] * inv;
-                        const bf16x4 o4 = __builtin_convertvector(v, bf16x4);
-                        *reinterpret_cast<bf16x4*>(orow + d) = o4;
-                    }
+                    for (int b = 0; b < 4; ++b) v[b] = acc[db][4 * a4 + b] * inv;
+                    *reinterpret_cast<bf16x4*>(orow + d) = __builtin_convertvector(v, bf16x4);
                 }
-            if (half == 0)
-                p.LSE[(size_t)head * p.lse_stride + row] = (m_run[nq] + __builtin_log2f(l_tot)) * LN2;
-        }
+            }
+        if (half == 0) p.LSE[(size_t)head * p.lse_stride + row] = (m_run + __builtin_log2f(l_tot)) * LN2;
     } else {
-        float* sa = p.st_acc + ((wg * NWAVE + w) * NQ) * (size_t)(DB * 16 * 64);
-        float* sm = p.st_ml + ((wg * NWAVE + w) * NQ) * (size_t)(2 * 64);
+        sm[lane] = m_run;
+        sm[64 + lane] = l_run;
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            sm[(nq * 2 + 0) * 64 + lane] = m_run[nq];
-            sm[(nq * 2 + 1) * 64 + lane] = l_run[nq];
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    sa[((nq * DB + db) * 16 + r) * 64 + lane] = acc[nq][db][r];
-        }
+            for (int r = 0; r < 16; ++r) sa[(db * 16 + r) * 64 + lane] = acc[db][r];
     }
 }
 
-template <int D>
-constexpr int nq_for() { return 2; }
-
 }  // namespace
 
-int fwd_q_tile(int D) { (void)D; return NWAVE * 32 * 2; }
+int fwd_q_tile(int D) { (void)D; return BQ; }
 
 size_t fwd_state_acc_bytes(int64_t n_q, int Hq, int D)
 {
@@ -299,11 +264,10 @@ void launch_fwd_sweep(const FwdArgs& a, hipStream_t st)
     k.g = a.Hq / a.Hkv;
     k.flags = a.flags;
     k.c = a.scale * LOG2E;
-    const int BQ = fwd_q_tile(a.D);
     dim3 grid((unsigned)((a.n_q / BQ) * a.Hq));
-    if (a.D == 128) fwd_sweep_kernel<128, 2><<<grid, 256, 0, st>>>(k);
-    else if (a.D == 80) fwd_sweep_kernel<80, 2><<<grid, 256, 0, st>>>(k);
-    else fwd_sweep_kernel<64, 2><<<grid, 256, 0, st>>>(k);
+    if (a.D == 128) fwd_sweep_kernel<128><<<grid, NTHREAD, 0, st>>>(k);
+    else if (a.D == 80) fwd_sweep_kernel<80><<<grid, NTHREAD, 0, st>>>(k);
+    else fwd_sweep_kernel<64><<<grid, NTHREAD, 0, st>>>(k);
 }
 
 }  // namespace fpdt

@@ -45,6 +45,8 @@ class Config:
 CONFIGS = {
     "tiny": Config("tiny", 1024, 256, 2, 2, 64, "f32"),
     "gpt2p7b_64k": Config("gpt2p7b_64k", 65536, 8192, 4, 4, 80, "bf16"),
+    # profiling-sized cut of the Llama-8B head share: one chunk, same kernels and tiles
+    "llama8b_64k": Config("llama8b_64k", 65536, 65536, 8, 2, 128, "bf16"),
     "llama8b_256k": Config("llama8b_256k", 262144, 65536, 8, 2, 128, "bf16"),
     "llama8b_2m": Config("llama8b_2m", 2097152, 65536, 8, 2, 128, "bf16", kv_on_host=True),
     "llama70b_1m": Config("llama70b_1m", 1048576, 65536, 8, 1, 128, "bf16", kv_on_host=True,
