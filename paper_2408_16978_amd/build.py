@@ -24,7 +24,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 
 def _compile(name: str) -> str:
     obj = os.path.join(BUILD_DIR, name.replace(".hip", ".o"))
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(SRC_DIR, name), "-o", obj]
+    extra = os.environ.get("FPDT_EXTRA_HIPCC_FLAGS", "").split()  # kernel experiments only
+    cmd = [HIPCC] + FLAGS + extra + ["-c", os.path.join(SRC_DIR, name), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s" % (name, r.stderr))

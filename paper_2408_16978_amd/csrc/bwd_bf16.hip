@@ -136,8 +136,12 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
 
     float pre_stat = 0.f;
     // Issue the loads of step `it` into ring slot `slot`: wave w copies fragments w, w+8, ...
+    // Query blocks are walked from the END of the range down to the diagonal: every workgroup
+    // of a launch then starts at the same block and the co-resident ones stay in step, so a
+    // block fetched by one workgroup is an L2 hit for the others (walking up from each
+    // workgroup's own diagonal would spread them over the whole sequence).
     auto issue = [&](int it, int slot) {
-        const int hh = it / n_qb, qb = qb_start + it % n_qb;
+        const int hh = it / n_qb, qb = n_qb_all - 1 - it % n_qb;
         const int head = kvh * p.g + hh;
         const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
 #pragma unroll
@@ -172,17 +176,15 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
         const u32x4* qt = on + NAT_U4;
         const u32x4* ot = qt + TR_U4;
         const float* st = stat[slot];
-        const int qb = qb_start + it % n_qb;
+        const int qb = n_qb_all - 1 - it % n_qb;
         const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
 
         if (qpos_b0 + 31 >= kpos_w0) {  // wave-uniform: some query of the block reaches this wave's keys
-            // S = Q K^T and dP = dO V^T as two interleaved accumulation chains
-            floatx16 s, dp;
+            // One accumulation chain at a time keeps the live registers under the 256 a wave
+            // may hold at two waves per SIMD: S -> p -> dV, then dP -> dS -> dK.
+            floatx16 s;
 #pragma unroll
-            for (int t = 0; t < DT; ++t) {
-                s = mfma32(as_bf16x8(qn[t * 64 + lane]), kf[t], t == 0 ? zero : s);
-                dp = mfma32(as_bf16x8(on[t * 64 + lane]), as_bf16x8(vmine[t * 64 + lane]), t == 0 ? zero : dp);
-            }
+            for (int t = 0; t < DT; ++t) s = mfma32(as_bf16x8(qn[t * 64 + lane]), kf[t], t == 0 ? zero : s);
             // p = exp2(s c - lse2), zero above the diagonal
 #pragma unroll
             for (int r = 0; r < 16; ++r)
@@ -192,14 +194,20 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
                 for (int r = 0; r < 16; ++r)
                     if (kpos > qpos_b0 + 8 * (r >> 2) + 4 * half + (r & 3)) s[r] = 0.f;
             }
-            const bf16x8 pf0 = pack_half<0>(s), pf1 = pack_half<1>(s);
-            // dV^T += dO^T p
+            {
+                const bf16x8 pf0 = pack_half<0>(s), pf1 = pack_half<1>(s);
+                // dV^T += dO^T p
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                dv[db] = mfma32(as_bf16x8(ot[(0 * DB + db) * 64 + lane]), pf0, dv[db]);
-                dv[db] = mfma32(as_bf16x8(ot[(1 * DB + db) * 64 + lane]), pf1, dv[db]);
+                for (int db = 0; db < DB; ++db) {
+                    dv[db] = mfma32(as_bf16x8(ot[(0 * DB + db) * 64 + lane]), pf0, dv[db]);
+                    dv[db] = mfma32(as_bf16x8(ot[(1 * DB + db) * 64 + lane]), pf1, dv[db]);
+                }
             }
-            // dS = p (dP - Delta)
+            // dP = dO V^T, dS = p (dP - Delta)
+            floatx16 dp;
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+                dp = mfma32(as_bf16x8(on[t * 64 + lane]), as_bf16x8(vmine[t * 64 + lane]), t == 0 ? zero : dp);
 #pragma unroll
             for (int r = 0; r < 16; ++r) dp[r] = s[r] * (dp[r] - st[32 + 8 * (r >> 2) + 4 * half + (r & 3)]);
             const bf16x8 df0 = pack_half<0>(dp), df1 = pack_half<1>(dp);

@@ -26,6 +26,7 @@ constexpr int NWAVE = 8;
 constexpr int NTHREAD = NWAVE * 64;
 constexpr int BQ = NWAVE * 32;  // query rows per workgroup
 constexpr int RING = 3;
+constexpr int PF = RING - 1;  // tiles in flight ahead of the one being computed
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -123,8 +124,9 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
             for (int r = 0; r < 16; ++r) acc[db][r] = sa[(db * 16 + r) * 64 + lane];
     }
 
-    if (n_tiles > 0) issue(0, 0);
-    if (n_tiles > 1) issue(1, 1);
+#pragma unroll
+    for (int i = 0; i < PF; ++i)
+        if (i < n_tiles) issue(i, i);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -133,20 +135,57 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
     const int64_t qpos = qpos_first + col;
     const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
+#ifdef FPDT_EXP_NO_LDS
+    bf16x8 kfr[KB][DT];
+    bf16x8 vfr[KB][2][DB];
+#endif
     for (int it = 0; it < n_tiles; ++it) {
-        if (it + 2 < n_tiles) issue(it + 2, (it + 2) % RING);
+        if (it + PF < n_tiles) issue(it + PF, (it + PF) % RING);
         const u32x4* ks = smem[it % RING];
         const u32x4* vs = ks + K_U4;
         const int64_t key0 = p.k_pos0 + (int64_t)it * BK;  // position of the tile's first key
 
         if (key0 <= qpos_last) {  // wave-uniform: tile not entirely above this wave's diagonal
-            // ---- S^T = K Q^T for the whole tile ----
+            // ---- S^T = K Q^T for the whole tile: all K fragments are requested up front so
+            // that the MFMA chain never waits on LDS latency ----
+#ifdef FPDT_EXP_NO_LDS
+            static_assert(true, "");
+            if (it == 0)
+#else
+            bf16x8 kfr[KB][DT];
+#endif
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int t = 0; t < DT; ++t) kfr[kb][t] = as_bf16x8(ks[(kb * DT + t) * 64 + lane]);
             floatx16 s[KB];
 #pragma unroll
             for (int t = 0; t < DT; ++t)
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
-                    s[kb] = mfma32(as_bf16x8(ks[(kb * DT + t) * 64 + lane]), qf[t], t == 0 ? zero : s[kb]);
+                for (int kb = 0; kb < KB; ++kb) s[kb] = mfma32(kfr[kb][t], qf[t], t == 0 ? zero : s[kb]);
+            __builtin_amdgcn_sched_group_barrier(0x100, KB * DT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, KB * DT, 0);
+            // V fragments are requested now and arrive under the softmax arithmetic
+#ifdef FPDT_EXP_NO_LDS
+            if (it == 0)
+#else
+            bf16x8 vfr[KB][2][DB];
+#endif
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) vfr[kb][s2][db] = as_bf16x8(vs[((kb * 2 + s2) * DB + db) * 64 + lane]);
+            __builtin_amdgcn_sched_group_barrier(0x100, KB * 2 * DB, 0);
+#ifdef FPDT_EXP_NO_SOFTMAX
+            bf16x8 pf[KB][2];
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                pf[kb][0] = pack_half<0>(s[kb]);
+                pf[kb][1] = pack_half<1>(s[kb]);
+            }
+#else
             // ---- online softmax, one query per lane ----
             if (key0 + BK - 1 > qpos_first) {  // wave-uniform: the tile straddles the diagonal
 #pragma unroll
@@ -188,6 +227,7 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
                 pf[kb][1] = pack_half<1>(s[kb]);
             }
             l_run += lsum;
+#endif
             // ---- O^T += V^T P^T ----
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb)
@@ -195,9 +235,11 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
                 for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
                     for (int db = 0; db < DB; ++db)
-                        acc[db] = mfma32(as_bf16x8(vs[((kb * 2 + s2) * DB + db) * 64 + lane]), pf[kb][s2], acc[db]);
+                        acc[db] = mfma32(vfr[kb][s2][db], pf[kb][s2], acc[db]);
         }
-        __builtin_amdgcn_s_waitcnt(0);  // tiles it+1, it+2 have landed in LDS
+        // tile it+1 must have landed; the loads of tile it+PF issued above may stay in flight
+        if (it + PF < n_tiles) wait_vmem_at_most<NFRAG / NWAVE>();
+        else wait_vmem_at_most<0>();
         __syncthreads();
     }
 

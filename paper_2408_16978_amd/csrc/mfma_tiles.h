@@ -37,6 +37,16 @@ __device__ __forceinline__ bf16x8 pack_half(const floatx16& v)
     return __builtin_convertvector(t, bf16x8);
 }
 
+// s_waitcnt that waits until at most N vector-memory loads (including direct-to-LDS
+// loads) of this wave are still in flight; LDS and export counters are left alone.
+// gfx9 encoding: vmcnt = simm16[15:14]:[3:0], expcnt = [6:4], lgkmcnt = [11:8].
+template <int N>
+__device__ __forceinline__ void wait_vmem_at_most()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
+}
+
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
 
 }  // namespace fpdt
