@@ -136,12 +136,13 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
 
     float pre_stat = 0.f;
     // Issue the loads of step `it` into ring slot `slot`: wave w copies fragments w, w+8, ...
-    // Query blocks are walked from the END of the range down to the diagonal: every workgroup
-    // of a launch then starts at the same block and the co-resident ones stay in step, so a
-    // block fetched by one workgroup is an L2 hit for the others (walking up from each
-    // workgroup's own diagonal would spread them over the whole sequence).
+    // Query blocks are walked from the END of the range down to the diagonal, the heads of the
+    // group innermost: every workgroup of a launch then visits (block, head) in the same order
+    // from the same starting point and the co-resident ones stay in step, so a block fetched
+    // by one workgroup is an L2 hit for the others (walking up from each workgroup's own
+    // diagonal, or head by head, spreads them over the whole sequence: 48x refetch measured).
     auto issue = [&](int it, int slot) {
-        const int hh = it / n_qb, qb = n_qb_all - 1 - it % n_qb;
+        const int hh = it % p.g, qb = n_qb_all - 1 - it / p.g;
         const int head = kvh * p.g + hh;
         const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
 #pragma unroll
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
         const u32x4* qt = on + NAT_U4;
         const u32x4* ot = qt + TR_U4;
         const float* st = stat[slot];
-        const int qb = n_qb_all - 1 - it % n_qb;
+        const int qb = n_qb_all - 1 - it / p.g;
         const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
 
         if (qpos_b0 + 31 >= kpos_w0) {  // wave-uniform: some query of the block reaches this wave's keys
@@ -330,12 +331,28 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
         for (int kb = 0; kb < KB; ++kb) {
             const int64_t key0 = p.k_pos0 + (int64_t)it * BK + 32 * kb;
             if (key0 <= qpos_last) {  // wave-uniform
+                // all NAT fragments of the block are requested before the MFMA chains start, the
+                // TR fragments right after them: they arrive under the chains / the arithmetic
+                bf16x8 kfr[DT], vfr[DT];
+#pragma unroll
+                for (int t = 0; t < DT; ++t) {
+                    kfr[t] = as_bf16x8(kn[(kb * DT + t) * 64 + lane]);
+                    vfr[t] = as_bf16x8(vn[(kb * DT + t) * 64 + lane]);
+                }
                 floatx16 s, dp;
 #pragma unroll
                 for (int t = 0; t < DT; ++t) {
-                    s = mfma32(as_bf16x8(kn[(kb * DT + t) * 64 + lane]), qf[t], t == 0 ? zero : s);
-                    dp = mfma32(as_bf16x8(vn[(kb * DT + t) * 64 + lane]), of[t], t == 0 ? zero : dp);
+                    s = mfma32(kfr[t], qf[t], t == 0 ? zero : s);
+                    dp = mfma32(vfr[t], of[t], t == 0 ? zero : dp);
                 }
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 * DT, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2 * DT, 0);
+                bf16x8 tfr[2][DB];
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) tfr[s2][db] = as_bf16x8(ktr[((kb * 2 + s2) * DB + db) * 64 + lane]);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], p.c, -lse2));
                 if (key0 + 31 > qpos_first) {  // wave-uniform: the block straddles the diagonal
@@ -348,12 +365,14 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
                 const bf16x8 df0 = pack_half<0>(dp), df1 = pack_half<1>(dp);
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    acc[db] = mfma32(as_bf16x8(ktr[((kb * 2 + 0) * DB + db) * 64 + lane]), df0, acc[db]);
-                    acc[db] = mfma32(as_bf16x8(ktr[((kb * 2 + 1) * DB + db) * 64 + lane]), df1, acc[db]);
+                    acc[db] = mfma32(tfr[0][db], df0, acc[db]);
+                    acc[db] = mfma32(tfr[1][db], df1, acc[db]);
                 }
             }
         }
-        __builtin_amdgcn_s_waitcnt(0);  // tiles it+1, it+2 have landed in LDS
+        // tile it+1 must have landed; the loads of tile it+2 issued above may stay in flight
+        if (it + 2 < n_tiles) wait_vmem_at_most<NFRAG / NWAVE>();
+        else wait_vmem_at_most<0>();
         __syncthreads();
     }
 
