@@ -17,6 +17,8 @@
 // fragments (fpdt_internal.h).  Both kernels run 8 waves per workgroup (two per SIMD, at
 // most 256 registers each, so one wave's exp / dS arithmetic runs under the other's MFMAs)
 // and stream their operands global -> LDS directly through a small ring.
+#include <type_traits>
+
 #include "fpdt_internal.h"
 #include "mfma_tiles.h"
 
@@ -236,6 +238,253 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
                 adk[(db * 16 + r) * 64 + lane] = dk[db][r];
                 adv[(db * 16 + r) * 64 + lane] = dv[db][r];
             }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// dK, dV with 64 keys per wave (one wave per SIMD, 4 waves, 256 keys per workgroup).
+//
+// A 32-key tile per wave needs one 1 KiB LDS fragment per MFMA, which LDS cannot deliver at
+// the MFMA rate; 64 keys per wave use every Q / dO fragment twice.  The 256 dK/dV accumulator
+// registers then have to live in AGPRs while the short-lived S / dP tiles must stay in
+// architectural VGPRs (VALU cannot read AGPRs): the compiler picks one form for all MFMAs of
+// a function, so the MFMAs are issued through inline assembly with explicit register classes,
+// and the wait states between an MFMA result and its first VALU reader, which the compiler
+// inserts for the builtin, are inserted by hand (s_nop).  The step is written in the order
+// it should issue: S chains | dP chains with the exp arithmetic in their shadow | dV MFMAs
+// with the dS arithmetic in their shadow | dK MFMAs.
+#define FPDT_MFMA_V0(d, a, b) \
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b))
+#define FPDT_MFMA_V(d, a, b) \
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b))
+#define FPDT_MFMA_A(d, a, b) \
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b))
+// >= 11 wait states between an 8-pass MFMA writing a VGPR and a VALU instruction reading it
+#define FPDT_MFMA_TO_VALU_NOPS() asm volatile("s_nop 7\n\ts_nop 4" ::: "memory")
+#define FPDT_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+template <int D>
+__global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
+{
+    constexpr int NW = 4, NK = 2;
+    constexpr int DT = D / 16, DP = (D + 31) / 32 * 32, DB = DP / 32;
+    constexpr int NAT_U4 = DT * 64, TR_U4 = 2 * DB * 64;
+    constexpr int SLOT_U4 = 2 * NAT_U4 + 2 * TR_U4;
+    constexpr int NFRAG = 2 * DT + 4 * DB;
+    constexpr int RING = 2;
+    constexpr int BKT = NW * 32 * NK;  // keys per workgroup
+    __shared__ u32x4 smem[RING][SLOT_U4];
+    __shared__ u32x4 vst[NW * NK * DT * 64];  // V NAT fragments of the workgroup's keys
+    __shared__ float stat[RING][64];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wu = __builtin_amdgcn_readfirstlane(w);
+    const int half = lane >> 5, col = lane & 31;
+    const int kvh = blockIdx.x % p.Hkv;
+    const int kt = blockIdx.x / p.Hkv;
+    const int k0 = kt * BKT, kw0 = k0 + 32 * NK * wu;
+    const int64_t kpos_w0 = p.k_pos0 + kw0;
+
+    bf16x8 kf[NK][DT];
+    u32x4* vmine = vst + wu * (NK * DT * 64);
+#pragma unroll
+    for (int kb = 0; kb < NK; ++kb) {
+        const size_t off = ((size_t)(kw0 + 32 * kb + col) * p.Hkv + kvh) * D + 8 * half;
+        const u32x4* vsrc = p.Vnat + ((size_t)kvh * p.kv_head_stride_blocks + (kw0 / 32 + kb)) * NAT_U4;
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+            kf[kb][t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.K + off + 16 * t));
+            frag_to_lds(vsrc + t * 64, vmine + (kb * DT + t) * 64, lane);
+        }
+    }
+
+    floatx16 dk[NK][DB], dv[NK][DB];
+    const size_t wg = blockIdx.x;
+    float* adk = p.acc_dk + ((wg * NW + w) * NK) * (size_t)(DB * 16 * 64);
+    float* adv = p.acc_dv + ((wg * NW + w) * NK) * (size_t)(DB * 16 * 64);
+    if (p.flags & ACC_LOAD) {
+#pragma unroll
+        for (int kb = 0; kb < NK; ++kb)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    dk[kb][db][r] = adk[((kb * DB + db) * 16 + r) * 64 + lane];
+                    dv[kb][db][r] = adv[((kb * DB + db) * 16 + r) * 64 + lane];
+                }
+    } else {
+#pragma unroll
+        for (int kb = 0; kb < NK; ++kb)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dk[kb][db][r] = dv[kb][db][r] = 0.f;
+    }
+
+    const int64_t qmin = p.k_pos0 + k0 - p.q_pos0;
+    const int qb_start = qmin > 0 ? (int)(qmin / 32) : 0;
+    const int n_qb_all = p.n_q / 32;
+    const int n_qb = n_qb_all > qb_start ? n_qb_all - qb_start : 0;
+    const int n_iter = n_qb * p.g;
+    // blocks whose first query precedes the workgroup's last key need the mask (for some wave)
+    const int64_t kpos_last = p.k_pos0 + k0 + BKT - 1;
+    int64_t dend = (kpos_last - p.q_pos0 + 31) / 32;
+    if (dend < qb_start) dend = qb_start;
+    if (dend > n_qb_all) dend = n_qb_all;
+    const int n_hot_iter = (n_qb_all - (int)dend) * p.g;  // walked first (descending order)
+
+    float pre_stat = 0.f;
+    auto issue = [&](int it, int slot) {
+        const int hh = it % p.g, qb = n_qb_all - 1 - it / p.g;
+        const int head = kvh * p.g + hh;
+        const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
+#pragma unroll
+        for (int f0 = 0; f0 < NFRAG; f0 += NW) {
+            const int f = f0 + wu;
+            if (f0 + NW <= NFRAG || f < NFRAG) {
+                const u32x4* src = f < DT ? p.Qnat + blk * NAT_U4 + f * 64
+                                 : f < 2 * DT ? p.dOnat + blk * NAT_U4 + (f - DT) * 64
+                                 : f < 2 * DT + 2 * DB ? p.Qtr + blk * TR_U4 + (f - 2 * DT) * 64
+                                                       : p.dOtr + blk * TR_U4 + (f - 2 * DT - 2 * DB) * 64;
+                frag_to_lds(src, &smem[slot][f * 64], lane);
+            }
+        }
+        if (tid < 32) pre_stat = p.LSE[(size_t)head * p.row_stat_stride + qb * 32 + tid] * LOG2E;
+        else if (tid < 64) pre_stat = p.Delta[(size_t)head * p.row_stat_stride + qb * 32 + tid - 32];
+    };
+
+    auto step = [&](auto masked_tag, int it) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const int slot = it % RING, nslot = (it + 1) % RING;
+        const bool more = it + 1 < n_iter;
+        if (more) issue(it + 1, nslot);
+        const u32x4* qn = smem[slot];
+        const u32x4* on = qn + NAT_U4;
+        const u32x4* qt = on + NAT_U4;
+        const u32x4* ot = qt + TR_U4;
+        const float* st = stat[slot];
+        const int qb = n_qb_all - 1 - it / p.g;
+        const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
+
+        if (!MASKED || qpos_b0 + 31 >= kpos_w0) {  // wave-uniform
+            // per-row statistics of the 16 query rows this lane sees
+            float lse2[16], dlt[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                lse2[r] = st[8 * (r >> 2) + 4 * half + (r & 3)];
+                dlt[r] = st[32 + 8 * (r >> 2) + 4 * half + (r & 3)];
+            }
+            floatx16 s0, s1, dp0, dp1;
+            // ---- A: S = Q K^T, two chains ----
+#pragma unroll
+            for (int t = 0; t < DT; ++t) {
+                const bf16x8 a = as_bf16x8(qn[t * 64 + lane]);
+                if (t == 0) {
+                    FPDT_MFMA_V0(s0, a, kf[0][t]);
+                    FPDT_MFMA_V0(s1, a, kf[1][t]);
+                } else {
+                    FPDT_MFMA_V(s0, a, kf[0][t]);
+                    FPDT_MFMA_V(s1, a, kf[1][t]);
+                }
+            }
+            FPDT_SCHED_FENCE();
+            // ---- B: dP = dO V^T, exp of S in the shadow of the MFMAs ----
+            bf16x8 pf[NK][2], df[NK][2];
+#pragma unroll
+            for (int t = 0; t < DT; ++t) {
+                const bf16x8 a = as_bf16x8(on[t * 64 + lane]);
+                const bf16x8 b0 = as_bf16x8(vmine[(0 * DT + t) * 64 + lane]);
+                const bf16x8 b1 = as_bf16x8(vmine[(1 * DT + t) * 64 + lane]);
+                if (t == 0) {
+                    FPDT_MFMA_V0(dp0, a, b0);
+                    FPDT_MFMA_V0(dp1, a, b1);
+                    FPDT_MFMA_TO_VALU_NOPS();  // s0, s1 are complete and readable from here on
+                } else {
+                    FPDT_MFMA_V(dp0, a, b0);
+                    FPDT_MFMA_V(dp1, a, b1);
+                }
+                FPDT_SCHED_FENCE();
+                // rows 2t, 2t+1 (D = 128: 8 steps x 2 rows = 16 rows) of both key blocks
+#pragma unroll
+                for (int r = (16 * t) / DT; r < (16 * (t + 1)) / DT; ++r) {
+                    float e0 = __builtin_amdgcn_exp2f(fmaf(s0[r], p.c, -lse2[r]));
+                    float e1 = __builtin_amdgcn_exp2f(fmaf(s1[r], p.c, -lse2[r]));
+                    if (MASKED) {
+                        const int64_t qp = qpos_b0 + 8 * (r >> 2) + 4 * half + (r & 3);
+                        if (kpos_w0 + col > qp) e0 = 0.f;
+                        if (kpos_w0 + 32 + col > qp) e1 = 0.f;
+                    }
+                    s0[r] = e0;
+                    s1[r] = e1;
+                }
+                FPDT_SCHED_FENCE();
+            }
+            pf[0][0] = pack_half<0>(s0); pf[1][0] = pack_half<0>(s1);
+            pf[0][1] = pack_half<1>(s0); pf[1][1] = pack_half<1>(s1);
+            FPDT_SCHED_FENCE();
+            // ---- C: dV^T += dO^T p, dS = p (dP - Delta) in the shadow ----
+#pragma unroll
+            for (int i = 0; i < 2 * DB; ++i) {
+                const int s2 = i / DB, db = i % DB;
+                const bf16x8 a = as_bf16x8(ot[(s2 * DB + db) * 64 + lane]);
+                FPDT_MFMA_A(dv[0][db], a, pf[0][s2]);
+                FPDT_MFMA_A(dv[1][db], a, pf[1][s2]);
+                if (i == 0) FPDT_MFMA_TO_VALU_NOPS();  // dp0, dp1 readable
+                FPDT_SCHED_FENCE();
+#pragma unroll
+                for (int r = (16 * i) / (2 * DB); r < (16 * (i + 1)) / (2 * DB); ++r) {
+                    dp0[r] = s0[r] * (dp0[r] - dlt[r]);
+                    dp1[r] = s1[r] * (dp1[r] - dlt[r]);
+                }
+                FPDT_SCHED_FENCE();
+            }
+            df[0][0] = pack_half<0>(dp0); df[1][0] = pack_half<0>(dp1);
+            df[0][1] = pack_half<1>(dp0); df[1][1] = pack_half<1>(dp1);
+            FPDT_SCHED_FENCE();
+            // ---- D: dK^T += Q^T dS ----
+#pragma unroll
+            for (int i = 0; i < 2 * DB; ++i) {
+                const int s2 = i / DB, db = i % DB;
+                const bf16x8 a = as_bf16x8(qt[(s2 * DB + db) * 64 + lane]);
+                FPDT_MFMA_A(dk[0][db], a, df[0][s2]);
+                FPDT_MFMA_A(dk[1][db], a, df[1][s2]);
+            }
+            FPDT_SCHED_FENCE();
+        }
+        if (more && tid < 64) stat[nslot][tid] = pre_stat;
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    };
+
+    if (n_iter > 0) {
+        issue(0, 0);
+        if (tid < 64) stat[0][tid] = pre_stat;
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    for (int it = 0; it < n_hot_iter; ++it) step(std::false_type{}, it);
+    for (int it = n_hot_iter; it < n_iter; ++it) step(std::true_type{}, it);
+
+    // the accumulators are read by ordinary instructions from here on
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    if (p.flags & ACC_FINAL) {
+#pragma unroll
+        for (int kb = 0; kb < NK; ++kb) {
+            const size_t off = ((size_t)(kw0 + 32 * kb + col) * p.Hkv + kvh) * D;
+            store_rows_bf16<D, DB>(dk[kb], p.scale, p.dK + off, half);
+            store_rows_bf16<D, DB>(dv[kb], 1.f, p.dV + off, half);
+        }
+    } else {
+#pragma unroll
+        for (int kb = 0; kb < NK; ++kb)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    adk[((kb * DB + db) * 16 + r) * 64 + lane] = dk[kb][db][r];
+                    adv[((kb * DB + db) * 16 + r) * 64 + lane] = dv[kb][db][r];
+                }
     }
 }
 
@@ -488,7 +737,7 @@ void launch_bwd_dkdv(const BwdArgs& a, hipStream_t st)
 {
     const BwdKernelArgs k = to_kernel_args(a);
     dim3 grid((unsigned)((a.n_k / bwd_k_tile(a.D)) * a.Hkv));
-    if (a.D == 128) bwd_dkdv_kernel<128><<<grid, NTHREAD, 0, st>>>(k);
+    if (a.D == 128) bwd_dkdv_kernel_w4<128><<<grid, 256, 0, st>>>(k);
     else if (a.D == 80) bwd_dkdv_kernel<80><<<grid, NTHREAD, 0, st>>>(k);
     else bwd_dkdv_kernel<64><<<grid, NTHREAD, 0, st>>>(k);
 }
