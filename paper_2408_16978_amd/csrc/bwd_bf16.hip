@@ -158,13 +158,14 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
                 frag_to_lds(src, &smem[slot][f * 64], lane);
             }
         }
-        if (tid < 32) pre_stat = p.LSE[(size_t)head * p.row_stat_stride + qb * 32 + tid] * LOG2E;
-        else if (tid < 64) pre_stat = p.Delta[(size_t)head * p.row_stat_stride + qb * 32 + tid - 32];
+        // raw value only: any arithmetic on it here would make the step wait for this load and,
+        // the counters being in order, for every operand copy issued before it
+        if (tid < 64) pre_stat = (tid < 32 ? p.LSE : p.Delta - 32)[(size_t)head * p.row_stat_stride + qb * 32 + tid];
     };
 
     if (n_iter > 0) {
         issue(0, 0);
-        if (tid < 64) stat[0][tid] = pre_stat;
+        if (tid < 64) stat[0][tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
                 dk[db] = mfma32(as_bf16x8(qt[(1 * DB + db) * 64 + lane]), df1, dk[db]);
             }
         }
-        if (more && tid < 64) stat[nslot][tid] = pre_stat;
+        if (more && tid < 64) stat[nslot][tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
         __builtin_amdgcn_s_waitcnt(0);  // the direct-to-LDS loads of step it+1 have landed
         __syncthreads();
     }
@@ -333,82 +334,95 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     if (dend > n_qb_all) dend = n_qb_all;
     const int n_hot_iter = (n_qb_all - (int)dend) * p.g;  // walked first (descending order)
 
+    static_assert(D == 128, "fragment schedule below is laid out for D = 128");
     float pre_stat = 0.f;
+    // wave w copies fragments w, w+4, ..., w+28 of the 32 that make a step; with D = 128 every
+    // operand has 8 fragments, so the operand of fragment f0 + w is known at compile time
     auto issue = [&](int it, int slot) {
         const int hh = it % p.g, qb = n_qb_all - 1 - it / p.g;
         const int head = kvh * p.g + hh;
         const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
+        const u32x4* base[4] = {p.Qnat + blk * NAT_U4, p.dOnat + blk * NAT_U4, p.Qtr + blk * TR_U4,
+                                p.dOtr + blk * TR_U4};
 #pragma unroll
         for (int f0 = 0; f0 < NFRAG; f0 += NW) {
             const int f = f0 + wu;
-            if (f0 + NW <= NFRAG || f < NFRAG) {
-                const u32x4* src = f < DT ? p.Qnat + blk * NAT_U4 + f * 64
-                                 : f < 2 * DT ? p.dOnat + blk * NAT_U4 + (f - DT) * 64
-                                 : f < 2 * DT + 2 * DB ? p.Qtr + blk * TR_U4 + (f - 2 * DT) * 64
-                                                       : p.dOtr + blk * TR_U4 + (f - 2 * DT - 2 * DB) * 64;
-                frag_to_lds(src, &smem[slot][f * 64], lane);
-            }
+            frag_to_lds(base[f0 / 8] + (f - 8 * (f0 / 8)) * 64, &smem[slot][f * 64], lane);
         }
-        if (tid < 32) pre_stat = p.LSE[(size_t)head * p.row_stat_stride + qb * 32 + tid] * LOG2E;
-        else if (tid < 64) pre_stat = p.Delta[(size_t)head * p.row_stat_stride + qb * 32 + tid - 32];
+        // raw value only: any arithmetic on it here would make the step wait for this load and,
+        // the counters being in order, for every operand copy issued before it
+        if (tid < 64) pre_stat = (tid < 32 ? p.LSE : p.Delta - 32)[(size_t)head * p.row_stat_stride + qb * 32 + tid];
     };
 
+    // One step.  The 32 A-operand fragments are consumed in the order Q-NAT 0..7, dO-NAT 0..7,
+    // dO-TR 0..7, Q-TR 0..7 (slot fragments 0..15, 24..31, 16..23); they are read from LDS four
+    // MFMA pairs ahead into a ring of six registers sets, so that a set is overwritten only
+    // two pairs after its last reader was issued.
     auto step = [&](auto masked_tag, int it) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         const int slot = it % RING, nslot = (it + 1) % RING;
         const bool more = it + 1 < n_iter;
         if (more) issue(it + 1, nslot);
-        const u32x4* qn = smem[slot];
-        const u32x4* on = qn + NAT_U4;
-        const u32x4* qt = on + NAT_U4;
-        const u32x4* ot = qt + TR_U4;
+        const u32x4* sl = smem[slot];
         const float* st = stat[slot];
         const int qb = n_qb_all - 1 - it / p.g;
         const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
 
         if (!MASKED || qpos_b0 + 31 >= kpos_w0) {  // wave-uniform
-            // per-row statistics of the 16 query rows this lane sees
-            float lse2[16], dlt[16];
+#define FPDT_AFRAG(u_) as_bf16x8(sl[((u_) < 16 ? (u_) : (u_) < 24 ? (u_) + 8 : (u_) - 8) * 64 + lane])
+            bf16x8 fr[6], vb0[3], vb1[3];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                lse2[r] = st[8 * (r >> 2) + 4 * half + (r & 3)];
-                dlt[r] = st[32 + 8 * (r >> 2) + 4 * half + (r & 3)];
-            }
+            for (int u = 0; u < 4; ++u) fr[u] = FPDT_AFRAG(u);
+            vb0[0] = as_bf16x8(vmine[(0 * DT + 0) * 64 + lane]);
+            vb1[0] = as_bf16x8(vmine[(1 * DT + 0) * 64 + lane]);
             floatx16 s0, s1, dp0, dp1;
+            bf16x8 pf[NK][2], df[NK][2];
+            // per-row statistics are read one chunk ahead of their use and BEFORE the fragment
+            // reads of that chunk, so the wait in front of the arithmetic never includes a
+            // 1 KiB fragment read (LDS returns in order)
+            auto stat2 = [&](int base, int r) {  // rows r, r+1 (r even): consecutive floats
+                return *reinterpret_cast<const float2*>(st + base + 8 * (r >> 2) + 4 * half + (r & 3));
+            };
+            float2 stat_nx = stat2(0, 0);
             // ---- A: S = Q K^T, two chains ----
 #pragma unroll
             for (int t = 0; t < DT; ++t) {
-                const bf16x8 a = as_bf16x8(qn[t * 64 + lane]);
+                const int u = t;
                 if (t == 0) {
-                    FPDT_MFMA_V0(s0, a, kf[0][t]);
-                    FPDT_MFMA_V0(s1, a, kf[1][t]);
+                    FPDT_MFMA_V0(s0, fr[u % 6], kf[0][t]);
+                    FPDT_MFMA_V0(s1, fr[u % 6], kf[1][t]);
                 } else {
-                    FPDT_MFMA_V(s0, a, kf[0][t]);
-                    FPDT_MFMA_V(s1, a, kf[1][t]);
+                    FPDT_MFMA_V(s0, fr[u % 6], kf[0][t]);
+                    FPDT_MFMA_V(s1, fr[u % 6], kf[1][t]);
                 }
+                fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
+                FPDT_SCHED_FENCE();
             }
-            FPDT_SCHED_FENCE();
             // ---- B: dP = dO V^T, exp of S in the shadow of the MFMAs ----
-            bf16x8 pf[NK][2], df[NK][2];
 #pragma unroll
             for (int t = 0; t < DT; ++t) {
-                const bf16x8 a = as_bf16x8(on[t * 64 + lane]);
-                const bf16x8 b0 = as_bf16x8(vmine[(0 * DT + t) * 64 + lane]);
-                const bf16x8 b1 = as_bf16x8(vmine[(1 * DT + t) * 64 + lane]);
+                const int u = DT + t;
+                const float2 lse = stat_nx;
+                stat_nx = t + 1 < DT ? stat2(0, 2 * t + 2) : stat2(32, 0);
                 if (t == 0) {
-                    FPDT_MFMA_V0(dp0, a, b0);
-                    FPDT_MFMA_V0(dp1, a, b1);
+                    FPDT_MFMA_V0(dp0, fr[u % 6], vb0[t % 3]);
+                    FPDT_MFMA_V0(dp1, fr[u % 6], vb1[t % 3]);
                     FPDT_MFMA_TO_VALU_NOPS();  // s0, s1 are complete and readable from here on
                 } else {
-                    FPDT_MFMA_V(dp0, a, b0);
-                    FPDT_MFMA_V(dp1, a, b1);
+                    FPDT_MFMA_V(dp0, fr[u % 6], vb0[t % 3]);
+                    FPDT_MFMA_V(dp1, fr[u % 6], vb1[t % 3]);
+                }
+                fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
+                if (t + 1 < DT) {
+                    vb0[(t + 1) % 3] = as_bf16x8(vmine[(0 * DT + t + 1) * 64 + lane]);
+                    vb1[(t + 1) % 3] = as_bf16x8(vmine[(1 * DT + t + 1) * 64 + lane]);
                 }
                 FPDT_SCHED_FENCE();
-                // rows 2t, 2t+1 (D = 128: 8 steps x 2 rows = 16 rows) of both key blocks
 #pragma unroll
-                for (int r = (16 * t) / DT; r < (16 * (t + 1)) / DT; ++r) {
-                    float e0 = __builtin_amdgcn_exp2f(fmaf(s0[r], p.c, -lse2[r]));
-                    float e1 = __builtin_amdgcn_exp2f(fmaf(s1[r], p.c, -lse2[r]));
+                for (int r = 2 * t; r < 2 * t + 2; ++r) {
+                    const float lse2 = (r & 1) ? lse.y : lse.x;
+                    float e0 = __builtin_amdgcn_exp2f(fmaf(s0[r], p.c, -lse2));
+                    float e1 = __builtin_amdgcn_exp2f(fmaf(s1[r], p.c, -lse2));
                     if (MASKED) {
                         const int64_t qp = qpos_b0 + 8 * (r >> 2) + 4 * half + (r & 3);
                         if (kpos_w0 + col > qp) e0 = 0.f;
@@ -417,48 +431,62 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                     s0[r] = e0;
                     s1[r] = e1;
                 }
+                if (t == 3) {
+                    pf[0][0] = pack_half<0>(s0);
+                    pf[1][0] = pack_half<0>(s1);
+                }
                 FPDT_SCHED_FENCE();
             }
-            pf[0][0] = pack_half<0>(s0); pf[1][0] = pack_half<0>(s1);
-            pf[0][1] = pack_half<1>(s0); pf[1][1] = pack_half<1>(s1);
+            pf[0][1] = pack_half<1>(s0);
+            pf[1][1] = pack_half<1>(s1);
             FPDT_SCHED_FENCE();
             // ---- C: dV^T += dO^T p, dS = p (dP - Delta) in the shadow ----
 #pragma unroll
             for (int i = 0; i < 2 * DB; ++i) {
+                const int u = 2 * DT + i;
                 const int s2 = i / DB, db = i % DB;
-                const bf16x8 a = as_bf16x8(ot[(s2 * DB + db) * 64 + lane]);
-                FPDT_MFMA_A(dv[0][db], a, pf[0][s2]);
-                FPDT_MFMA_A(dv[1][db], a, pf[1][s2]);
+                const float2 dl = stat_nx;
+                if (i + 1 < 2 * DB) stat_nx = stat2(32, 2 * i + 2);
+                FPDT_MFMA_A(dv[0][db], fr[u % 6], pf[0][s2]);
+                FPDT_MFMA_A(dv[1][db], fr[u % 6], pf[1][s2]);
                 if (i == 0) FPDT_MFMA_TO_VALU_NOPS();  // dp0, dp1 readable
+                fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
                 FPDT_SCHED_FENCE();
 #pragma unroll
-                for (int r = (16 * i) / (2 * DB); r < (16 * (i + 1)) / (2 * DB); ++r) {
-                    dp0[r] = s0[r] * (dp0[r] - dlt[r]);
-                    dp1[r] = s1[r] * (dp1[r] - dlt[r]);
+                for (int r = 2 * i; r < 2 * i + 2; ++r) {
+                    const float dlt = (r & 1) ? dl.y : dl.x;
+                    dp0[r] = s0[r] * (dp0[r] - dlt);
+                    dp1[r] = s1[r] * (dp1[r] - dlt);
+                }
+                if (i == 3) {
+                    df[0][0] = pack_half<0>(dp0);
+                    df[1][0] = pack_half<0>(dp1);
                 }
                 FPDT_SCHED_FENCE();
             }
-            df[0][0] = pack_half<0>(dp0); df[1][0] = pack_half<0>(dp1);
-            df[0][1] = pack_half<1>(dp0); df[1][1] = pack_half<1>(dp1);
+            df[0][1] = pack_half<1>(dp0);
+            df[1][1] = pack_half<1>(dp1);
             FPDT_SCHED_FENCE();
             // ---- D: dK^T += Q^T dS ----
 #pragma unroll
             for (int i = 0; i < 2 * DB; ++i) {
+                const int u = 2 * DT + 2 * DB + i;
                 const int s2 = i / DB, db = i % DB;
-                const bf16x8 a = as_bf16x8(qt[(s2 * DB + db) * 64 + lane]);
-                FPDT_MFMA_A(dk[0][db], a, df[0][s2]);
-                FPDT_MFMA_A(dk[1][db], a, df[1][s2]);
+                FPDT_MFMA_A(dk[0][db], fr[u % 6], df[0][s2]);
+                FPDT_MFMA_A(dk[1][db], fr[u % 6], df[1][s2]);
+                if (u + 4 < 32) fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
+                FPDT_SCHED_FENCE();
             }
-            FPDT_SCHED_FENCE();
+#undef FPDT_AFRAG
         }
-        if (more && tid < 64) stat[nslot][tid] = pre_stat;
+        if (more && tid < 64) stat[nslot][tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     };
 
     if (n_iter > 0) {
         issue(0, 0);
-        if (tid < 64) stat[0][tid] = pre_stat;
+        if (tid < 64) stat[0][tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();

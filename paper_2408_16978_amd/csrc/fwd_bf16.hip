@@ -60,7 +60,11 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
     constexpr int V_U4 = KB * 2 * DB * 64;  // u32x4 per V tile
     constexpr int T_U4 = K_U4 + V_U4;
     constexpr int KFRAG = KB * DT, NFRAG = KFRAG + KB * 2 * DB;  // 1 KiB fragments per tile
-    __shared__ u32x4 smem[RING][T_U4];
+    // One LDS array per ring slot: distinct objects carry distinct alias scopes, which is what
+    // lets the compiler see that a direct-to-LDS copy into one slot does not feed the reads of
+    // another (with a single array every LDS read waits for all copies in flight).
+    static_assert(RING == 3, "the tile loop below is unrolled over three slots");
+    __shared__ u32x4 ring0[T_U4], ring1[T_U4], ring2[T_U4];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wu = __builtin_amdgcn_readfirstlane(w);
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
     const u32x4* vbase = p.Vtr + (size_t)kvh * p.kv_head_stride_blocks * (2 * DB * 64);
 
     // Copy tile `it` into ring slot `slot`: wave w moves fragments w, w+8, ...
-    auto issue = [&](int it, int slot) {
+    auto issue = [&](int it, u32x4* slot) {
         const u32x4* ksrc = kbase + (size_t)it * K_U4;
         const u32x4* vsrc = vbase + (size_t)it * V_U4;
 #pragma unroll
@@ -90,7 +94,7 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
             const int f = f0 + wu;
             if (f0 + NWAVE <= NFRAG || f < NFRAG) {
                 const u32x4* src = f < KFRAG ? ksrc + f * 64 : vsrc + (f - KFRAG) * 64;
-                frag_to_lds(src, &smem[slot][f * 64], lane);
+                frag_to_lds(src, slot + f * 64, lane);
             }
         }
     };
@@ -124,9 +128,8 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
             for (int r = 0; r < 16; ++r) acc[db][r] = sa[(db * 16 + r) * 64 + lane];
     }
 
-#pragma unroll
-    for (int i = 0; i < PF; ++i)
-        if (i < n_tiles) issue(i, i);
+    if (n_tiles > 0) issue(0, ring0);
+    if (n_tiles > 1) issue(1, ring1);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -135,25 +138,16 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
     const int64_t qpos = qpos_first + col;
     const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-#ifdef FPDT_EXP_NO_LDS
-    bf16x8 kfr[KB][DT];
-    bf16x8 vfr[KB][2][DB];
-#endif
-    for (int it = 0; it < n_tiles; ++it) {
-        if (it + PF < n_tiles) issue(it + PF, (it + PF) % RING);
-        const u32x4* ks = smem[it % RING];
+    // One tile: compute on slot `ks`, prefetch tile it+PF into slot `pf_slot`.
+    auto tile = [&](int it, const u32x4* ks, u32x4* pf_slot) {
+        if (it + PF < n_tiles) issue(it + PF, pf_slot);
         const u32x4* vs = ks + K_U4;
         const int64_t key0 = p.k_pos0 + (int64_t)it * BK;  // position of the tile's first key
 
         if (key0 <= qpos_last) {  // wave-uniform: tile not entirely above this wave's diagonal
             // ---- S^T = K Q^T for the whole tile: all K fragments are requested up front so
             // that the MFMA chain never waits on LDS latency ----
-#ifdef FPDT_EXP_NO_LDS
-            static_assert(true, "");
-            if (it == 0)
-#else
             bf16x8 kfr[KB][DT];
-#endif
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -166,11 +160,7 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
             __builtin_amdgcn_sched_group_barrier(0x100, KB * DT, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, KB * DT, 0);
             // V fragments are requested now and arrive under the softmax arithmetic
-#ifdef FPDT_EXP_NO_LDS
-            if (it == 0)
-#else
             bf16x8 vfr[KB][2][DB];
-#endif
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -178,14 +168,6 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
 #pragma unroll
                     for (int db = 0; db < DB; ++db) vfr[kb][s2][db] = as_bf16x8(vs[((kb * 2 + s2) * DB + db) * 64 + lane]);
             __builtin_amdgcn_sched_group_barrier(0x100, KB * 2 * DB, 0);
-#ifdef FPDT_EXP_NO_SOFTMAX
-            bf16x8 pf[KB][2];
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                pf[kb][0] = pack_half<0>(s[kb]);
-                pf[kb][1] = pack_half<1>(s[kb]);
-            }
-#else
             // ---- online softmax, one query per lane ----
             if (key0 + BK - 1 > qpos_first) {  // wave-uniform: the tile straddles the diagonal
 #pragma unroll
@@ -227,7 +209,6 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
                 pf[kb][1] = pack_half<1>(s[kb]);
             }
             l_run += lsum;
-#endif
             // ---- O^T += V^T P^T ----
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb)
@@ -240,7 +221,12 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
         // tile it+1 must have landed; the loads of tile it+PF issued above may stay in flight
         if (it + PF < n_tiles) wait_vmem_at_most<NFRAG / NWAVE>();
         else wait_vmem_at_most<0>();
-        __syncthreads();
+        barrier_no_fence();
+    };
+    for (int it = 0; it < n_tiles; it += 3) {
+        tile(it, ring0, ring2);
+        if (it + 1 < n_tiles) tile(it + 1, ring1, ring0);
+        if (it + 2 < n_tiles) tile(it + 2, ring2, ring1);
     }
 
     // ---- epilogue ----

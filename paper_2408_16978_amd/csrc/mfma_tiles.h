@@ -47,6 +47,19 @@ __device__ __forceinline__ void wait_vmem_at_most()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
 }
 
+// Workgroup barrier WITHOUT the memory fence of __syncthreads().  The fence makes a wave wait
+// for every vector-memory operation it has in flight, i.e. also for the direct-to-LDS copies
+// of tiles that are not needed yet.  The caller waits for exactly what the next tile needs
+// (wait_vmem_at_most) and for its own LDS traffic; the empty asm statements keep the compiler
+// from moving memory accesses across the barrier.
+__device__ __forceinline__ void barrier_no_fence()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): own LDS reads / writes are done
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
 
 }  // namespace fpdt
