@@ -45,14 +45,6 @@ struct BwdKernelArgs {
     uint16_t* dQ; uint16_t* dK; uint16_t* dV;
 };
 
-// Direct global -> LDS copy of one 1 KiB fragment by one wave (no VGPR staging): lane l's
-// 16 bytes land at dst + 16 l.
-__device__ __forceinline__ void frag_to_lds(const u32x4* src, u32x4* dst_wave_uniform, int lane)
-{
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + lane),
-                                     (__attribute__((address_space(3))) void*)dst_wave_uniform, 16, 0, 0);
-}
-
 // Store a transposed accumulator tile set (lane = one row, registers = channels) as bf16
 // into a [rows, H, D] tensor.
 template <int D, int DB>
@@ -85,9 +77,10 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
     constexpr int NFRAG = 2 * DT + 4 * DB;
     constexpr int RING = 2;
     constexpr int BKT = NWAVE * 32;  // keys per workgroup
-    __shared__ u32x4 smem[RING][SLOT_U4];
+    static_assert(RING == 2, "the step loop below alternates between two slots");
+    __shared__ u32x4 slot0[SLOT_U4], slot1[SLOT_U4];
     __shared__ u32x4 vst[NWAVE * DT * 64];  // V NAT fragments of the workgroup's keys
-    __shared__ float stat[RING][64];        // [0,32): LSE*log2e, [32,64): Delta of the staged block
+    __shared__ float stat0[64], stat1[64];  // [0,32): LSE*log2e, [32,64): Delta of the staged block
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wu = __builtin_amdgcn_readfirstlane(w);
@@ -143,7 +136,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
     // from the same starting point and the co-resident ones stay in step, so a block fetched
     // by one workgroup is an L2 hit for the others (walking up from each workgroup's own
     // diagonal, or head by head, spreads them over the whole sequence: 48x refetch measured).
-    auto issue = [&](int it, int slot) {
+    auto issue = [&](int it, u32x4* slot) {
         const int hh = it % p.g, qb = n_qb_all - 1 - it / p.g;
         const int head = kvh * p.g + hh;
         const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
@@ -155,7 +148,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
                                  : f < 2 * DT ? p.dOnat + blk * NAT_U4 + (f - DT) * 64
                                  : f < 2 * DT + 2 * DB ? p.Qtr + blk * TR_U4 + (f - 2 * DT) * 64
                                                        : p.dOtr + blk * TR_U4 + (f - 2 * DT - 2 * DB) * 64;
-                frag_to_lds(src, &smem[slot][f * 64], lane);
+                frag_to_lds(src, slot + f * 64, lane);
             }
         }
         // raw value only: any arithmetic on it here would make the step wait for this load and,
@@ -164,22 +157,20 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
     };
 
     if (n_iter > 0) {
-        issue(0, 0);
-        if (tid < 64) stat[0][tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
+        issue(0, slot0);
+        if (tid < 64) stat0[tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
     const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int it = 0; it < n_iter; ++it) {
-        const int slot = it % RING, nslot = (it + 1) % RING;
+    // One step: compute on (qn, st), stage step it+1 into (nslot, nst).
+    auto step = [&](int it, const u32x4* qn, const float* st, u32x4* nslot, float* nst) {
         const bool more = it + 1 < n_iter;
         if (more) issue(it + 1, nslot);
-        const u32x4* qn = smem[slot];
         const u32x4* on = qn + NAT_U4;
         const u32x4* qt = on + NAT_U4;
         const u32x4* ot = qt + TR_U4;
-        const float* st = stat[slot];
         const int qb = n_qb_all - 1 - it / p.g;
         const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
 
@@ -222,9 +213,13 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
                 dk[db] = mfma32(as_bf16x8(qt[(1 * DB + db) * 64 + lane]), df1, dk[db]);
             }
         }
-        if (more && tid < 64) stat[nslot][tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
-        __builtin_amdgcn_s_waitcnt(0);  // the direct-to-LDS loads of step it+1 have landed
-        __syncthreads();
+        if (more && tid < 64) nst[tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
+        wait_vmem_at_most<0>();  // the direct-to-LDS loads of step it+1 have landed
+        barrier_no_fence();
+    };
+    for (int it = 0; it < n_iter; it += 2) {
+        step(it, slot0, stat0, slot1, stat1);
+        if (it + 1 < n_iter) step(it + 1, slot1, stat1, slot0, stat0);
     }
 
     if (p.flags & ACC_FINAL) {
@@ -274,9 +269,10 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     constexpr int NFRAG = 2 * DT + 4 * DB;
     constexpr int RING = 2;
     constexpr int BKT = NW * 32 * NK;  // keys per workgroup
-    __shared__ u32x4 smem[RING][SLOT_U4];
+    static_assert(RING == 2, "the step loops below alternate between two slots");
+    __shared__ u32x4 slot0[SLOT_U4], slot1[SLOT_U4];
     __shared__ u32x4 vst[NW * NK * DT * 64];  // V NAT fragments of the workgroup's keys
-    __shared__ float stat[RING][64];
+    __shared__ float stat0[64], stat1[64];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wu = __builtin_amdgcn_readfirstlane(w);
@@ -286,6 +282,38 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     const int k0 = kt * BKT, kw0 = k0 + 32 * NK * wu;
     const int64_t kpos_w0 = p.k_pos0 + kw0;
 
+    floatx16 dk[NK][DB], dv[NK][DB];
+    const size_t wg = blockIdx.x;
+    float* adk = p.acc_dk + ((wg * NW + w) * NK) * (size_t)(DB * 16 * 64);
+    float* adv = p.acc_dv + ((wg * NW + w) * NK) * (size_t)(DB * 16 * 64);
+    if (p.flags & ACC_LOAD) {
+#pragma unroll
+        for (int kb = 0; kb < NK; ++kb)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    dk[kb][db][r] = adk[((kb * DB + db) * 16 + r) * 64 + lane];
+                    dv[kb][db][r] = adv[((kb * DB + db) * 16 + r) * 64 + lane];
+                }
+                // into accumulation registers right away, one tile pair at a time: left to the
+                // first MFMA that uses them, all 256 values would sit in architectural registers
+                asm volatile("" : "+a"(dk[kb][db]), "+a"(dv[kb][db]));
+            }
+    } else {
+#pragma unroll
+        for (int kb = 0; kb < NK; ++kb)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dk[kb][db][r] = dv[kb][db][r] = 0.f;
+                asm volatile("" : "+a"(dk[kb][db]), "+a"(dv[kb][db]));
+            }
+    }
+
+    // loaded after the accumulators so that nothing has to be parked in scratch across their
+    // initialisation (a reload in front of the loop would put a full vector-memory wait, which
+    // also covers the operand copies in flight, at its first use inside the loop)
     bf16x8 kf[NK][DT];
     u32x4* vmine = vst + wu * (NK * DT * 64);
 #pragma unroll
@@ -297,29 +325,6 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
             kf[kb][t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.K + off + 16 * t));
             frag_to_lds(vsrc + t * 64, vmine + (kb * DT + t) * 64, lane);
         }
-    }
-
-    floatx16 dk[NK][DB], dv[NK][DB];
-    const size_t wg = blockIdx.x;
-    float* adk = p.acc_dk + ((wg * NW + w) * NK) * (size_t)(DB * 16 * 64);
-    float* adv = p.acc_dv + ((wg * NW + w) * NK) * (size_t)(DB * 16 * 64);
-    if (p.flags & ACC_LOAD) {
-#pragma unroll
-        for (int kb = 0; kb < NK; ++kb)
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    dk[kb][db][r] = adk[((kb * DB + db) * 16 + r) * 64 + lane];
-                    dv[kb][db][r] = adv[((kb * DB + db) * 16 + r) * 64 + lane];
-                }
-    } else {
-#pragma unroll
-        for (int kb = 0; kb < NK; ++kb)
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) dk[kb][db][r] = dv[kb][db][r] = 0.f;
     }
 
     const int64_t qmin = p.k_pos0 + k0 - p.q_pos0;
@@ -338,7 +343,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     float pre_stat = 0.f;
     // wave w copies fragments w, w+4, ..., w+28 of the 32 that make a step; with D = 128 every
     // operand has 8 fragments, so the operand of fragment f0 + w is known at compile time
-    auto issue = [&](int it, int slot) {
+    auto issue = [&](int it, u32x4* slot) {
         const int hh = it % p.g, qb = n_qb_all - 1 - it / p.g;
         const int head = kvh * p.g + hh;
         const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
@@ -347,7 +352,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
 #pragma unroll
         for (int f0 = 0; f0 < NFRAG; f0 += NW) {
             const int f = f0 + wu;
-            frag_to_lds(base[f0 / 8] + (f - 8 * (f0 / 8)) * 64, &smem[slot][f * 64], lane);
+            frag_to_lds(base[f0 / 8] + (f - 8 * (f0 / 8)) * 64, slot + f * 64, lane);
         }
         // raw value only: any arithmetic on it here would make the step wait for this load and,
         // the counters being in order, for every operand copy issued before it
@@ -358,13 +363,10 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     // dO-TR 0..7, Q-TR 0..7 (slot fragments 0..15, 24..31, 16..23); they are read from LDS four
     // MFMA pairs ahead into a ring of six registers sets, so that a set is overwritten only
     // two pairs after its last reader was issued.
-    auto step = [&](auto masked_tag, int it) {
+    auto step = [&](auto masked_tag, int it, const u32x4* sl, const float* st, u32x4* nslot, float* nst) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const int slot = it % RING, nslot = (it + 1) % RING;
         const bool more = it + 1 < n_iter;
         if (more) issue(it + 1, nslot);
-        const u32x4* sl = smem[slot];
-        const float* st = stat[slot];
         const int qb = n_qb_all - 1 - it / p.g;
         const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
 
@@ -479,20 +481,39 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
             }
 #undef FPDT_AFRAG
         }
-        if (more && tid < 64) stat[nslot][tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
+        if (more && tid < 64) nst[tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
+        wait_vmem_at_most<0>();  // the direct-to-LDS loads of step it+1 have landed
+        barrier_no_fence();
     };
 
     if (n_iter > 0) {
-        issue(0, 0);
-        if (tid < 64) stat[0][tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
+        issue(0, slot0);
+        if (tid < 64) stat0[tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    for (int it = 0; it < n_hot_iter; ++it) step(std::false_type{}, it);
-    for (int it = n_hot_iter; it < n_iter; ++it) step(std::true_type{}, it);
+    // Touch the stationary K fragments in front of each loop: whatever the register allocator
+    // parked in scratch is reloaded and waited for HERE; a reload whose first use is inside the
+    // loop would put a full vector-memory wait (operand copies in flight included) in every step.
+    auto pin_kf = [&]() {
+#pragma unroll
+        for (int kb = 0; kb < NK; ++kb)
+#pragma unroll
+            for (int t = 0; t < DT; ++t) asm volatile("" ::"v"(kf[kb][t]));
+    };
+    // the unmasked steps come first (descending walk); an odd count leaves the ring on slot 1
+    const int n_hot_even = n_hot_iter & ~1;
+    pin_kf();
+    for (int it = 0; it < n_hot_even; it += 2) {
+        step(std::false_type{}, it, slot0, stat0, slot1, stat1);
+        step(std::false_type{}, it + 1, slot1, stat1, slot0, stat0);
+    }
+    pin_kf();
+    for (int it = n_hot_even; it < n_iter; it += 2) {
+        step(std::true_type{}, it, slot0, stat0, slot1, stat1);
+        if (it + 1 < n_iter) step(std::true_type{}, it + 1, slot1, stat1, slot0, stat0);
+    }
 
     // the accumulators are read by ordinary instructions from here on
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
@@ -530,7 +551,8 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
     constexpr int SLOT_U4 = 2 * NAT_U4 + TR_U4;
     constexpr int NATF = KB * DT, NFRAG = 2 * NATF + KB * 2 * DB;
     constexpr int RING = 3;
-    __shared__ u32x4 smem[RING][SLOT_U4];
+    static_assert(RING == 3, "the tile loop below is unrolled over three slots");
+    __shared__ u32x4 ring0[SLOT_U4], ring1[SLOT_U4], ring2[SLOT_U4];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wu = __builtin_amdgcn_readfirstlane(w);
@@ -551,7 +573,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
     const u32x4* vnb = p.Vnat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
     const u32x4* ktb = p.Ktr + (size_t)kvh * p.kv_head_stride_blocks * (2 * DB * 64);
 
-    auto issue = [&](int it, int slot) {
+    auto issue = [&](int it, u32x4* slot) {
 #pragma unroll
         for (int f0 = 0; f0 < NFRAG; f0 += NWAVE) {
             const int f = f0 + wu;
@@ -559,7 +581,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
                 const u32x4* src = f < NATF ? knb + (size_t)it * NAT_U4 + f * 64
                                  : f < 2 * NATF ? vnb + (size_t)it * NAT_U4 + (f - NATF) * 64
                                                 : ktb + (size_t)it * TR_U4 + (f - 2 * NATF) * 64;
-                frag_to_lds(src, &smem[slot][f * 64], lane);
+                frag_to_lds(src, slot + f * 64, lane);
             }
         }
     };
@@ -592,16 +614,16 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
             for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
     }
 
-    if (n_tiles > 0) issue(0, 0);
-    if (n_tiles > 1) issue(1, 1);
+    if (n_tiles > 0) issue(0, ring0);
+    if (n_tiles > 1) issue(1, ring1);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
     const int64_t qpos_first = p.q_pos0 + qw0, qpos_last = qpos_first + 31, qpos = qpos_first + col;
     const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int it = 0; it < n_tiles; ++it) {
-        if (it + 2 < n_tiles) issue(it + 2, (it + 2) % RING);
-        const u32x4* kn = smem[it % RING];
+    // One tile: compute on slot `kn`, prefetch tile it+2 into slot `pf_slot`.
+    auto tile = [&](int it, const u32x4* kn, u32x4* pf_slot) {
+        if (it + 2 < n_tiles) issue(it + 2, pf_slot);
         const u32x4* vn = kn + NAT_U4;
         const u32x4* ktr = vn + NAT_U4;
 #pragma unroll
@@ -650,7 +672,12 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
         // tile it+1 must have landed; the loads of tile it+2 issued above may stay in flight
         if (it + 2 < n_tiles) wait_vmem_at_most<NFRAG / NWAVE>();
         else wait_vmem_at_most<0>();
-        __syncthreads();
+        barrier_no_fence();
+    };
+    for (int it = 0; it < n_tiles; it += 3) {
+        tile(it, ring0, ring2);
+        if (it + 1 < n_tiles) tile(it + 1, ring1, ring0);
+        if (it + 2 < n_tiles) tile(it + 2, ring2, ring1);
     }
 
     if (p.flags & ACC_FINAL) {

@@ -46,12 +46,6 @@ struct FwdKernelArgs {
     float c;  // scale * log2(e)
 };
 
-__device__ __forceinline__ void frag_to_lds(const u32x4* src, u32x4* dst_wave_uniform, int lane)
-{
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + lane),
-                                     (__attribute__((address_space(3))) void*)dst_wave_uniform, 16, 0, 0);
-}
-
 template <int D>
 __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
 {
@@ -60,9 +54,7 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
     constexpr int V_U4 = KB * 2 * DB * 64;  // u32x4 per V tile
     constexpr int T_U4 = K_U4 + V_U4;
     constexpr int KFRAG = KB * DT, NFRAG = KFRAG + KB * 2 * DB;  // 1 KiB fragments per tile
-    // One LDS array per ring slot: distinct objects carry distinct alias scopes, which is what
-    // lets the compiler see that a direct-to-LDS copy into one slot does not feed the reads of
-    // another (with a single array every LDS read waits for all copies in flight).
+    // one LDS array per ring slot
     static_assert(RING == 3, "the tile loop below is unrolled over three slots");
     __shared__ u32x4 ring0[T_U4], ring1[T_U4], ring2[T_U4];
 
@@ -170,13 +162,16 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
             __builtin_amdgcn_sched_group_barrier(0x100, KB * 2 * DB, 0);
             // ---- online softmax, one query per lane ----
             if (key0 + BK - 1 > qpos_first) {  // wave-uniform: the tile straddles the diagonal
+                // key index within the tile vs this lane's query, in 32 bits: a key is masked
+                // when 32 kb + 8 (r / 4) + r % 4 + 4 half > qpos - key0
+                int64_t d = qpos - key0;
+                d = d < -1 ? -1 : d > BK ? BK : d;
+                const int rel = (int)d - 4 * half;
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int64_t kpos = key0 + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
-                        if (kpos > qpos) s[kb][r] = -INFINITY;
-                    }
+                    for (int r = 0; r < 16; ++r)
+                        if (32 * kb + 8 * (r >> 2) + (r & 3) > rel) s[kb][r] = -INFINITY;
             }
             float mx = fmaxf(s[0][0], s[0][1]);
 #pragma unroll

@@ -60,6 +60,30 @@ __device__ __forceinline__ void barrier_no_fence()
     asm volatile("" ::: "memory");
 }
 
+// Direct global -> LDS copy of one 1 KiB fragment by one wave (no VGPR staging): lane l's
+// 16 bytes, read from src + 16 l, land at dst + 16 l.  src and dst are wave-uniform.
+//
+// Issued through inline assembly on purpose.  The compiler's wait-count insertion treats the
+// builtin form as an access to both memory and LDS: while one is in flight, every wait for an
+// LDS read becomes a wait for ALL LDS reads (no read-ahead under the MFMAs), and LDS reads
+// that may alias the copy wait for it.  Hidden from that pass, the copy is tracked by hand:
+// callers drain it with wait_vmem_at_most<N>() before the barrier that publishes the tile.
+// (Waits the compiler computes for its own vector loads then count too few operations in
+// flight, which only makes them stricter.)
+__device__ __forceinline__ void frag_to_lds(const u32x4* src_wave_uniform, u32x4* dst_wave_uniform, int lane)
+{
+    const unsigned lds = __builtin_amdgcn_readfirstlane(
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)dst_wave_uniform);
+    const uint64_t a = (uint64_t)(uintptr_t)src_wave_uniform;  // into scalar registers, both halves
+    // (readfirstlane returns a signed int: widen each half as unsigned)
+    const uint64_t src = ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(a >> 32)) << 32) |
+                         (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)a);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds), "v"(lane * 16), "s"(src)
+                 : "memory");  // m0 is reserved: the compiler sets it right before each use of its own
+}
+
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
 
 }  // namespace fpdt
