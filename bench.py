@@ -19,6 +19,16 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 
+# HBM bytes (read + written) per launch of each kernel, from two rocprofv3 --pmc runs of this
+# script (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the plain
+# 1 GiB copy kernel of --calibrate-copy (2.0 and 1.0).  A profiler measurement, not a live one:
+# only the workload it was taken on has an entry.
+HBM_TRAFFIC_PER_LAUNCH = {
+    ("llama8b_2m", "fwd_sweep"): 2.79e9,
+    ("llama8b_2m", "bwd_dkdv"): 4.84e9,
+    ("llama8b_2m", "bwd_dq"): 4.22e9,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -30,6 +40,9 @@ def parse():
     ap.add_argument("--no-link-probe", action="store_true")
     ap.add_argument("--resident-compare", action="store_true",
                     help="also time the same pair schedule with K/V resident (exposed copy time)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel (reference for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -159,7 +172,8 @@ def main():
     dom_flops = gemms[dom] * per_gemm * args.steps
     achieved = dom_flops / (prof[dom]["total_ms"] * 1e-3) / 1e12 if prof[dom]["total_ms"] > 0 else 0.0
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                "traffic": HBM_TRAFFIC_PER_LAUNCH.get((cfg.name, dom)),
                 "avg_launch_ms": prof[dom]["total_ms"] / max(1, prof[dom]["launches"]),
                 "launches": prof[dom]["launches"]}
 
@@ -207,6 +221,13 @@ def main():
         res_ms = (time.perf_counter() - t1) * 1e3
         out["offload"]["resident_pairwise_ms"] = res_ms
         out["offload"]["exposed_copy_ms"] = ms_per_step - res_ms
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        torch.add(a, 0.0, out=b)  # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
     if not args.no_cpu_baseline:
         src_k = Kdev if cfg.kv_on_host else bufs.K
         src_v = Vdev if cfg.kv_on_host else bufs.V
