@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=1)
     ap.add_argument("--warmup", type=int, default=0)
     ap.add_argument("--config", default="llama8b_2m")
+    ap.add_argument("--chunk", type=int, default=0, help="override the workload's chunk size")
+    ap.add_argument("--seq", type=int, default=0, help="override the workload's sequence length")
+    ap.add_argument("--offload", choices=["none", "kv", "kv+act"], default=None,
+                    help="override which tensors live in pinned host memory")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-link-probe", action="store_true")
     ap.add_argument("--resident-compare", action="store_true",
@@ -102,6 +106,20 @@ def main():
     from paper_2408_16978_amd import binding as B, inputs, runner
 
     cfg = inputs.CONFIGS[args.config]
+    if args.chunk or args.seq or args.offload is not None:
+        import dataclasses
+        over = {}
+        if args.chunk:
+            over["chunk"] = args.chunk
+        if args.seq:
+            over["S"] = args.seq
+        if args.offload is not None:
+            over["kv_on_host"] = args.offload != "none"
+            over["act_on_host"] = args.offload == "kv+act"
+        cfg = dataclasses.replace(cfg, **over)
+        cfg = dataclasses.replace(cfg, name="%s[S=%d,chunk=%d,offload=%s]" % (
+            args.config, cfg.S, cfg.chunk,
+            "kv+act" if cfg.act_on_host else "kv" if cfg.kv_on_host else "none"))
     torch.cuda.set_device(0)
     seed = 2024
     Q, K, V, dO = inputs.make_qkvdo(cfg.S, cfg.Hq, cfg.Hkv, cfg.D, cfg.dtype, seed, device="cuda")

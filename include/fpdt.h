@@ -93,6 +93,23 @@ size_t fpdt_attn_workspace_bytes(int64_t S, int64_t chunk, int Hq, int Hkv, int 
                                  unsigned flags, int is_bwd);
 
 /*
+ * Chunk size to use for a sequence of S tokens (Sec. 5.3: a chunk that is too small
+ * starves the GPU, one that is too large wastes device memory on chunk buffers; the paper
+ * settles on 64K tokens).  Returns the largest chunk c <= 131072 with S % c == 0, c a
+ * multiple of FPDT_CHUNK_MULTIPLE (bf16 only), for which both workspaces
+ * (fpdt_attn_workspace_bytes with is_bwd = 0 and 1) fit in max_workspace_bytes (0 = no
+ * limit).  Larger is better up to that cap: one launch of the dK/dV kernel has
+ * chunk / 256 * Hkv workgroups, which fills the 256 compute units only from 32K tokens on
+ * at two KV heads, and every chunk pair costs a fixed launch, state load and state store
+ * (measured on the Llama-8B head share at S = 256K with K/V offloaded: 409, 645, 857, 895,
+ * 889 TFLOP/s at 8K, 16K, 32K, 64K, 128K tokens; at S = 2M: 908, 877, 916 at 32K, 64K, 128K).
+ * Returns 0 when the arguments are invalid or no chunk fits (fpdt_last_error says which).
+ * Host logic only: no device is touched.
+ */
+int64_t fpdt_attn_pick_chunk(int64_t S, int Hq, int Hkv, int D, int dtype, unsigned flags,
+                             size_t max_workspace_bytes);
+
+/*
  * Forward (Sec. 4.1, Figs. 4-5).  For every query chunk m = 0..u-1, fold in the
  * key/value chunks i = 0..m (earlier chunks first, the masked diagonal pair last),
  * carrying the running row maximum, row sum and un-normalised output in fp32, and

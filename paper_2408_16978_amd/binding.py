@@ -45,6 +45,8 @@ def load():
                                ctypes.c_float, ctypes.c_size_t)
     L.fpdt_attn_workspace_bytes.restype = sz
     L.fpdt_attn_workspace_bytes.argtypes = [i64, i64, ci, ci, ci, ci, cu, ci]
+    L.fpdt_attn_pick_chunk.restype = i64
+    L.fpdt_attn_pick_chunk.argtypes = [i64, ci, ci, ci, ci, cu, sz]
     L.fpdt_attn_fwd.restype = ci
     L.fpdt_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, ci, ci, ci, cf, ci, cu, vp, sz, vp]
     L.fpdt_attn_bwd.restype = ci
@@ -117,6 +119,11 @@ def fpdt_profile_read(kind: int):
 
 def fpdt_attn_workspace_bytes(S, chunk, Hq, Hkv, D, dtype, flags=0, is_bwd=False) -> int:
     return int(load().fpdt_attn_workspace_bytes(S, chunk, Hq, Hkv, D, dtype, flags, int(is_bwd)))
+
+
+def fpdt_attn_pick_chunk(S, Hq, Hkv, D, dtype, flags=0, max_workspace_bytes=0) -> int:
+    """Recommended chunk size (0 if none: see fpdt_last_error)."""
+    return int(load().fpdt_attn_pick_chunk(S, Hq, Hkv, D, dtype, flags, max_workspace_bytes))
 
 
 def fpdt_attn_fwd(Q, K, V, O, LSE, chunk, scale, flags=0, workspace=None, stream=None):

@@ -696,6 +696,30 @@ size_t fpdt_attn_workspace_bytes(int64_t S, int64_t chunk, int Hq, int Hkv, int 
     return is_bwd ? plan_bwd(p, nullptr).total : plan_fwd(p, nullptr).total;
 }
 
+int64_t fpdt_attn_pick_chunk(int64_t S, int Hq, int Hkv, int D, int dtype, unsigned flags,
+                             size_t max_workspace_bytes)
+{
+    g_err.clear();
+    const int64_t step = dtype == FPDT_DTYPE_BF16 ? FPDT_CHUNK_MULTIPLE : 1;
+    const int64_t cap = 131072;
+    auto fits = [&](int64_t c) {
+        Problem q;
+        if (validate_scalars(q, S, c, Hq, Hkv, D, 1.f, dtype, flags) != FPDT_OK) return false;
+        if (!max_workspace_bytes) return true;
+        return plan_fwd(q, nullptr).total <= max_workspace_bytes && plan_bwd(q, nullptr).total <= max_workspace_bytes;
+    };
+    // divisors of S that are multiples of `step`, from the cap downwards: the first that fits
+    for (int64_t c = (S < cap ? S : cap) / step * step; c >= step; c -= step) {
+        if (S % c == 0 && fits(c)) { g_err.clear(); return c; }
+    }
+    Problem q;  // say why: the arguments themselves, or the workspace limit
+    if (validate_scalars(q, S, step, Hq, Hkv, D, 1.f, dtype, flags) == FPDT_OK || S % step != 0) {
+        if (S > 0 && S % step != 0) fail(FPDT_ERR_UNSUPPORTED, "S=%lld has no chunk size that is a multiple of %lld", (long long)S, (long long)step);
+        else fail(FPDT_ERR_WORKSPACE, "no chunk size of S=%lld fits in %zu bytes of workspace", (long long)S, max_workspace_bytes);
+    }
+    return 0;
+}
+
 int fpdt_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int64_t S,
                   int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype, unsigned flags,
                   void* workspace, size_t workspace_bytes, void* stream)

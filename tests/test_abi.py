@@ -100,3 +100,27 @@ def test_workspace_sizes():
     c = ws(1 << 20, 65536, 8, 1, 128, bf, B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST, True)
     d = ws(1 << 21, 65536, 8, 1, 128, bf, B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST, True)
     assert d - c == 2 * (1 << 20) * 1 * 128 * 4
+
+
+def test_pick_chunk_host_logic(lib):
+    BF, F32 = B.FPDT_DTYPE_BF16, B.FPDT_DTYPE_F32
+    # largest divisor of S up to the 128K cap
+    assert B.fpdt_attn_pick_chunk(2097152, 8, 2, 128, BF, B.FPDT_KV_ON_HOST) == 131072
+    assert B.fpdt_attn_pick_chunk(65536, 4, 4, 80, BF) == 65536
+    assert B.fpdt_attn_pick_chunk(768 * 256, 8, 2, 128, BF) == 98304      # 3 * 2^15: divisor, multiple of 256
+    assert B.fpdt_attn_pick_chunk(1024, 2, 2, 64, F32) == 1024
+    # the answer is always a legal chunk for the entry points and respects the workspace limit
+    for S, flags in ((2097152, B.FPDT_KV_ON_HOST), (1048576, B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST), (262144, 0)):
+        full = B.fpdt_attn_pick_chunk(S, 8, 2, 128, BF, flags)
+        need = max(B.fpdt_attn_workspace_bytes(S, full, 8, 2, 128, BF, flags, b) for b in (False, True))
+        assert need > 0
+        c = B.fpdt_attn_pick_chunk(S, 8, 2, 128, BF, flags, need - 1)
+        if c:
+            assert c < full and S % c == 0 and c % 256 == 0
+            assert max(B.fpdt_attn_workspace_bytes(S, c, 8, 2, 128, BF, flags, b) for b in (False, True)) <= need - 1
+        assert B.fpdt_attn_pick_chunk(S, 8, 2, 128, BF, flags, need) == full
+    # no chunk: reasons are reported
+    assert B.fpdt_attn_pick_chunk(1000, 2, 2, 64, BF) == 0 and "multiple" in B.fpdt_last_error()
+    assert B.fpdt_attn_pick_chunk(0, 2, 2, 64, BF) == 0 and B.fpdt_last_error() != ""
+    assert B.fpdt_attn_pick_chunk(4096, 3, 2, 64, BF) == 0 and "Hq" in B.fpdt_last_error()
+    assert B.fpdt_attn_pick_chunk(4096, 2, 2, 64, BF, 0, 16) == 0 and "workspace" in B.fpdt_last_error()
