@@ -26,6 +26,16 @@ def lib():
         L.fpdt_oracle_rows.argtypes = [dp, dp, ip, ctypes.c_int64, dp, dp, ctypes.c_int64,
                                        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
                                        dp, dp, dp, dp]
+        bp = ctypes.POINTER(ctypes.c_uint8)
+        L.fpdt_oracle_rows_blocksparse.restype = ctypes.c_int
+        L.fpdt_oracle_rows_blocksparse.argtypes = [dp, dp, ip, ctypes.c_int64, dp, dp, ctypes.c_int64,
+                                                   ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                   ctypes.c_double, ctypes.c_int64, bp, dp, dp, dp, dp]
+        L.fpdt_oracle_cols_blocksparse.restype = ctypes.c_int
+        L.fpdt_oracle_cols_blocksparse.argtypes = [dp, dp, dp, dp, ctypes.c_int64, dp, dp, ip,
+                                                   ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                                   ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                                   ctypes.c_int64, bp, dp, dp]
         L.fpdt_oracle_cols.restype = ctypes.c_int
         L.fpdt_oracle_cols.argtypes = [dp, dp, dp, dp, ctypes.c_int64, dp, dp, ip, ctypes.c_int64,
                                        ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -51,10 +61,21 @@ def _ip(a):
     return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
 
 
-def rows(Qr, K, V, row_idx, scale, dOr=None):
+def _mask(chunk_mask, chunk, S):
+    """(chunk, contiguous uint8 [u,u] or None, its ctypes pointer or None)"""
+    if chunk_mask is None:
+        return 0, None, None
+    m = np.ascontiguousarray(np.asarray(chunk_mask) != 0, dtype=np.uint8)
+    assert chunk and S % chunk == 0 and m.shape == (S // chunk, S // chunk)
+    return int(chunk), m, m.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+
+
+def rows(Qr, K, V, row_idx, scale, dOr=None, chunk=None, chunk_mask=None):
     """Quantities indexed by a query row, for the listed rows only.
 
     Qr, dOr: [n, Hq, D] (rows `row_idx` of Q and dO); K, V: [S, Hkv, D].
+    chunk, chunk_mask [u,u]: block-sparse variant (query chunk m reads key chunk
+    i <= m iff chunk_mask[m, i]); None = dense.
     Returns dict with O [n,Hq,D], LSE [Hq,n] and, if dOr is given,
     Delta [Hq,n] and dQ [n,Hq,D].
     """
@@ -72,8 +93,14 @@ def rows(Qr, K, V, row_idx, scale, dOr=None):
         dQ = np.empty((n, Hq, D))
     else:
         Delta = dQ = None
-    rc = lib().fpdt_oracle_rows(_dp(Qr), _dp(dOr), _ip(idx), n, _dp(K), _dp(V), S, Hq, Hkv, D,
-                                float(scale), _dp(O), _dp(LSE), _dp(Delta), _dp(dQ))
+    c, m, mp = _mask(chunk_mask, chunk, S)
+    if m is None:
+        rc = lib().fpdt_oracle_rows(_dp(Qr), _dp(dOr), _ip(idx), n, _dp(K), _dp(V), S, Hq, Hkv, D,
+                                    float(scale), _dp(O), _dp(LSE), _dp(Delta), _dp(dQ))
+    else:
+        rc = lib().fpdt_oracle_rows_blocksparse(_dp(Qr), _dp(dOr), _ip(idx), n, _dp(K), _dp(V), S,
+                                                Hq, Hkv, D, float(scale), c, mp, _dp(O), _dp(LSE),
+                                                _dp(Delta), _dp(dQ))
     if rc != 0:
         raise ValueError("fpdt_oracle_rows rejected its arguments")
     out = {"O": O, "LSE": np.ascontiguousarray(LSE.T)}
@@ -83,7 +110,7 @@ def rows(Qr, K, V, row_idx, scale, dOr=None):
     return out
 
 
-def cols(Qw, dOw, LSEw, Deltaw, row_base, Kc, Vc, col_idx, S, scale):
+def cols(Qw, dOw, LSEw, Deltaw, row_base, Kc, Vc, col_idx, S, scale, chunk=None, chunk_mask=None):
     """dK, dV for the listed key rows.
 
     Qw, dOw: [S-row_base, Hq, D] query rows row_base..S-1; LSEw, Deltaw:
@@ -99,9 +126,15 @@ def cols(Qw, dOw, LSEw, Deltaw, row_base, Kc, Vc, col_idx, S, scale):
     assert W == S - row_base and lse.shape == (W, Hq) and delta.shape == (W, Hq)
     dK = np.empty((n, Hkv, D))
     dV = np.empty((n, Hkv, D))
-    rc = lib().fpdt_oracle_cols(_dp(Qw), _dp(dOw), _dp(lse), _dp(delta), int(row_base), _dp(Kc),
-                                _dp(Vc), _ip(idx), n, int(S), Hq, Hkv, D, float(scale), _dp(dK),
-                                _dp(dV))
+    c, m, mp = _mask(chunk_mask, chunk, S)
+    if m is None:
+        rc = lib().fpdt_oracle_cols(_dp(Qw), _dp(dOw), _dp(lse), _dp(delta), int(row_base), _dp(Kc),
+                                    _dp(Vc), _ip(idx), n, int(S), Hq, Hkv, D, float(scale), _dp(dK),
+                                    _dp(dV))
+    else:
+        rc = lib().fpdt_oracle_cols_blocksparse(_dp(Qw), _dp(dOw), _dp(lse), _dp(delta),
+                                                int(row_base), _dp(Kc), _dp(Vc), _ip(idx), n, int(S),
+                                                Hq, Hkv, D, float(scale), c, mp, _dp(dK), _dp(dV))
     if rc != 0:
         raise ValueError("fpdt_oracle_cols rejected its arguments")
     return dK, dV
@@ -114,11 +147,12 @@ def attn_fwd(Q, K, V, scale):
     return r["O"], r["LSE"]
 
 
-def attn_fwd_bwd(Q, K, V, dO, scale):
+def attn_fwd_bwd(Q, K, V, dO, scale, chunk=None, chunk_mask=None):
     """Full forward + backward: dict O, LSE, Delta, dQ, dK, dV."""
     S = Q.shape[0]
-    r = rows(Q, K, V, np.arange(S), scale, dOr=dO)
-    dK, dV = cols(Q, dO, r["LSE"], r["Delta"], 0, K, V, np.arange(S), S, scale)
+    r = rows(Q, K, V, np.arange(S), scale, dOr=dO, chunk=chunk, chunk_mask=chunk_mask)
+    dK, dV = cols(Q, dO, r["LSE"], r["Delta"], 0, K, V, np.arange(S), S, scale, chunk=chunk,
+                  chunk_mask=chunk_mask)
     r["dK"], r["dV"] = dK, dV
     return r
 

@@ -30,6 +30,15 @@
  * Layout: tensors are row-major [rows, heads, D]; per-row scalars are
  * [rows, Hq].  Everything is double.
  *
+ * Block-sparse variant (Sec. 5.5: with sparse attention only part of the key /
+ * value chunks is fetched, the queries are always the whole sequence).  The
+ * sequence is cut into chunks of `chunk` rows and a u x u byte matrix says
+ * which key chunks a query chunk reads: key j is allowed for query i iff
+ * j <= i and mask[(i / chunk) * u + j / chunk] != 0.  Every sum over j above
+ * (and over i for dK, dV) then runs over the allowed pairs only; nothing else
+ * changes.  mask == NULL is the dense definition.  The diagonal entries of the
+ * mask must be set, so that every query row keeps at least its own key.
+ *
  * Two entry points: a row evaluator (everything that is indexed by a query
  * row) and a column evaluator (everything indexed by a key row).  The full
  * problem is "all rows, then all columns"; sampled checks at large S call the
@@ -69,13 +78,31 @@ static double dot(const double *a, const double *b, int n)
  *   LSE, Delta : [n, Hq]   out
  * Returns 0, or 1 on bad arguments / allocation failure.
  */
-int fpdt_oracle_rows(const double *Qr, const double *dOr, const int64_t *rows, int64_t n,
-                     const double *K, const double *V, int64_t S, int Hq, int Hkv, int D,
-                     double scale, double *O, double *LSE, double *Delta, double *dQ)
+/* key j allowed for query i (j <= i is the caller's loop bound) */
+static int allowed(const uint8_t *mask, int64_t chunk, int64_t u, int64_t i, int64_t j)
+{
+    return !mask || mask[(i / chunk) * u + j / chunk] != 0;
+}
+
+static int mask_ok(const uint8_t *mask, int64_t chunk, int64_t S)
+{
+    if (!mask) return 1;
+    if (chunk <= 0 || S % chunk != 0) return 0;
+    const int64_t u = S / chunk;
+    for (int64_t m = 0; m < u; ++m)
+        if (!mask[m * u + m]) return 0;
+    return 1;
+}
+
+int fpdt_oracle_rows_blocksparse(const double *Qr, const double *dOr, const int64_t *rows, int64_t n,
+                                 const double *K, const double *V, int64_t S, int Hq, int Hkv,
+                                 int D, double scale, int64_t chunk, const uint8_t *mask,
+                                 double *O, double *LSE, double *Delta, double *dQ)
 {
     if (!Qr || !rows || !K || !V || !O || !LSE || n < 0 || S <= 0 || Hq <= 0 || Hkv <= 0 ||
-        D <= 0 || Hq % Hkv != 0)
+        D <= 0 || Hq % Hkv != 0 || !mask_ok(mask, chunk, S))
         return 1;
+    const int64_t u = mask ? S / chunk : 1;
     if (dOr && (!Delta || !dQ)) return 1;
     for (int64_t r = 0; r < n; ++r)
         if (rows[r] < 0 || rows[r] >= S) return 1;
@@ -100,15 +127,18 @@ int fpdt_oracle_rows(const double *Qr, const double *dOr, const int64_t *rows, i
                     /* scores of the allowed keys j <= i, and their maximum */
                     double m = -INFINITY;
                     for (int64_t j = 0; j <= i; ++j) {
+                        if (!allowed(mask, chunk, u, i, j)) continue;
                         p[j] = scale * dot(q, K + ((size_t)j * Hkv + kv) * D, D);
                         if (p[j] > m) m = p[j];
                     }
                     double l = 0.0;
-                    for (int64_t j = 0; j <= i; ++j) l += exp(p[j] - m);
+                    for (int64_t j = 0; j <= i; ++j)
+                        if (allowed(mask, chunk, u, i, j)) l += exp(p[j] - m);
                     const double lse = m + log(l);
                     LSE[(size_t)r * Hq + h] = lse;
                     for (int d = 0; d < D; ++d) o[d] = 0.0;
                     for (int64_t j = 0; j <= i; ++j) {
+                        if (!allowed(mask, chunk, u, i, j)) continue;
                         p[j] = exp(p[j] - lse); /* probabilities from here on */
                         const double *v = V + ((size_t)j * Hkv + kv) * D;
                         const double pj = p[j];
@@ -121,6 +151,7 @@ int fpdt_oracle_rows(const double *Qr, const double *dOr, const int64_t *rows, i
                     Delta[(size_t)r * Hq + h] = delta;
                     for (int d = 0; d < D; ++d) gq[d] = 0.0;
                     for (int64_t j = 0; j <= i; ++j) {
+                        if (!allowed(mask, chunk, u, i, j)) continue;
                         const double dp = dot(go, V + ((size_t)j * Hkv + kv) * D, D);
                         const double ds = p[j] * (dp - delta);
                         const double *k = K + ((size_t)j * Hkv + kv) * D;
@@ -133,6 +164,14 @@ int fpdt_oracle_rows(const double *Qr, const double *dOr, const int64_t *rows, i
         free(p);
     }
     return fail;
+}
+
+int fpdt_oracle_rows(const double *Qr, const double *dOr, const int64_t *rows, int64_t n,
+                     const double *K, const double *V, int64_t S, int Hq, int Hkv, int D,
+                     double scale, double *O, double *LSE, double *Delta, double *dQ)
+{
+    return fpdt_oracle_rows_blocksparse(Qr, dOr, rows, n, K, V, S, Hq, Hkv, D, scale, 0, NULL, O,
+                                        LSE, Delta, dQ);
 }
 
 /*
@@ -148,14 +187,17 @@ int fpdt_oracle_rows(const double *Qr, const double *dOr, const int64_t *rows, i
  * it, so a row window that starts at or before the smallest listed column
  * holds every contribution.
  */
-int fpdt_oracle_cols(const double *Q, const double *dO, const double *LSE, const double *Delta,
-                     int64_t row_base, const double *Kc, const double *Vc, const int64_t *cols,
-                     int64_t n, int64_t S, int Hq, int Hkv, int D, double scale, double *dK,
-                     double *dV)
+int fpdt_oracle_cols_blocksparse(const double *Q, const double *dO, const double *LSE,
+                                 const double *Delta, int64_t row_base, const double *Kc,
+                                 const double *Vc, const int64_t *cols, int64_t n, int64_t S, int Hq,
+                                 int Hkv, int D, double scale, int64_t chunk, const uint8_t *mask,
+                                 double *dK, double *dV)
 {
     if (!Q || !dO || !LSE || !Delta || !Kc || !Vc || !cols || !dK || !dV || n < 0 || S <= 0 ||
-        Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0 || row_base < 0 || row_base >= S)
+        Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0 || row_base < 0 || row_base >= S ||
+        !mask_ok(mask, chunk, S))
         return 1;
+    const int64_t u = mask ? S / chunk : 1;
     for (int64_t c = 0; c < n; ++c)
         if (cols[c] < row_base || cols[c] >= S) return 1;
     const int g = Hq / Hkv;
@@ -170,6 +212,7 @@ int fpdt_oracle_cols(const double *Q, const double *dO, const double *LSE, const
             for (int d = 0; d < D; ++d) gk[d] = gv[d] = 0.0;
             for (int h = kv * g; h < (kv + 1) * g; ++h) {
                 for (int64_t i = j; i < S; ++i) {
+                    if (!allowed(mask, chunk, u, i, j)) continue;
                     const size_t ri = (size_t)(i - row_base);
                     const double *q = Q + (ri * Hq + h) * D;
                     const double *go = dO + (ri * Hq + h) * D;
@@ -187,4 +230,13 @@ int fpdt_oracle_cols(const double *Q, const double *dO, const double *LSE, const
         }
     }
     return 0;
+}
+
+int fpdt_oracle_cols(const double *Q, const double *dO, const double *LSE, const double *Delta,
+                     int64_t row_base, const double *Kc, const double *Vc, const int64_t *cols,
+                     int64_t n, int64_t S, int Hq, int Hkv, int D, double scale, double *dK,
+                     double *dV)
+{
+    return fpdt_oracle_cols_blocksparse(Q, dO, LSE, Delta, row_base, Kc, Vc, cols, n, S, Hq, Hkv, D,
+                                        scale, 0, NULL, dK, dV);
 }

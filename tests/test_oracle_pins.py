@@ -21,8 +21,9 @@ def rand(S, Hq, Hkv, D, seed):
             r.standard_normal((S, Hkv, D)), r.standard_normal((S, Hq, D)))
 
 
-def torch_reference(Q, K, V, dO, scale):
-    """Library pin: masked softmax + autograd in fp64 (no formula of ours)."""
+def torch_reference(Q, K, V, dO, scale, allowed=None):
+    """Library pin: masked softmax + autograd in fp64 (no formula of ours).
+    allowed: optional [S,S] boolean matrix ANDed with the causal mask."""
     q = torch.tensor(Q, requires_grad=True)
     k = torch.tensor(K, requires_grad=True)
     v = torch.tensor(V, requires_grad=True)
@@ -32,6 +33,8 @@ def torch_reference(Q, K, V, dO, scale):
     vv = v.repeat_interleave(g, dim=1)
     s = scale * torch.einsum("ihd,jhd->hij", q, kk)
     mask = torch.ones(S, S, dtype=torch.bool).tril()
+    if allowed is not None:
+        mask = mask & torch.tensor(allowed)
     s = s.masked_fill(~mask, float("-inf"))
     lse = torch.logsumexp(s, dim=-1)
     o = torch.einsum("hij,jhd->ihd", torch.softmax(s, dim=-1), vv)
@@ -251,3 +254,95 @@ def test_oracle_rejects_bad_arguments():
     Q, K, V, dO = rand(8, 2, 2, 4, 11)
     with pytest.raises(ValueError):
         definition.rows(Q[:1], K, V, np.array([8]), 1.0)
+
+
+# ---- block-sparse variant (Sec. 5.5): a chunk-level mask on top of the causal one ----
+def _chunk_masks(u, seed):
+    r = np.random.default_rng(seed)
+    m = np.tril(r.random((u, u)) < 0.5)
+    np.fill_diagonal(m, True)
+    return m
+
+
+@pytest.mark.parametrize("S,chunk,Hq,Hkv,D", [(48, 8, 2, 1, 8), (40, 10, 4, 2, 5), (36, 12, 1, 1, 16)])
+def test_blocksparse_against_torch_autograd(S, chunk, Hq, Hkv, D):
+    Q, K, V, dO = rand(S, Hq, Hkv, D, 11)
+    cm = _chunk_masks(S // chunk, 12)
+    assert not cm[np.tril_indices(S // chunk)].all()  # something below the diagonal is dropped
+    allowed = np.kron(cm, np.ones((chunk, chunk), dtype=bool))
+    r = definition.attn_fwd_bwd(Q, K, V, dO, 0.41, chunk=chunk, chunk_mask=cm)
+    O, LSE, dQ, dK, dV = torch_reference(Q, K, V, dO, 0.41, allowed=allowed)
+    for name, ref in (("O", O), ("LSE", LSE), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        np.testing.assert_allclose(r[name], ref, rtol=1e-11, atol=1e-12, err_msg=name)
+
+
+def test_blocksparse_full_mask_is_the_dense_definition():
+    S, chunk = 64, 16
+    Q, K, V, dO = rand(S, 4, 2, 8, 13)
+    dense = definition.attn_fwd_bwd(Q, K, V, dO, 0.3)
+    full = definition.attn_fwd_bwd(Q, K, V, dO, 0.3, chunk=chunk, chunk_mask=np.ones((4, 4)))
+    for name in ("O", "LSE", "Delta", "dQ", "dK", "dV"):
+        assert np.array_equal(dense[name], full[name]), name
+    # entries above the diagonal are never read
+    junk = np.tril(np.ones((4, 4))) + np.triu(np.ones((4, 4)), 1) * 7
+    r = definition.attn_fwd_bwd(Q, K, V, dO, 0.3, chunk=chunk, chunk_mask=junk)
+    assert np.array_equal(dense["dK"], r["dK"])
+
+
+def test_blocksparse_reduces_to_dense_attention_over_the_kept_chunks():
+    """Rows of query chunk m equal dense causal attention over the concatenation of the key
+    chunks it keeps (they all precede it, so only its own chunk is masked inside)."""
+    S, chunk, Hq, Hkv, D = 60, 12, 2, 2, 6
+    u = S // chunk
+    Q, K, V, dO = rand(S, Hq, Hkv, D, 14)
+    cm = _chunk_masks(u, 15)
+    sp = definition.rows(Q, K, V, np.arange(S), 0.5, dOr=dO, chunk=chunk, chunk_mask=cm)
+    for m in range(u):
+        kept = [i for i in range(m + 1) if cm[m, i]]
+        sel = np.concatenate([np.arange(i * chunk, (i + 1) * chunk) for i in kept])
+        rows_m = np.arange(m * chunk, (m + 1) * chunk)
+        local = np.arange((len(kept) - 1) * chunk, len(kept) * chunk)  # chunk m comes last
+        d = definition.rows(Q[rows_m], K[sel], V[sel], local, 0.5, dOr=dO[rows_m])
+        np.testing.assert_allclose(sp["O"][rows_m], d["O"], atol=1e-14)
+        np.testing.assert_allclose(sp["LSE"][:, rows_m], d["LSE"], atol=1e-14)
+        np.testing.assert_allclose(sp["dQ"][rows_m], d["dQ"], atol=1e-13)
+
+
+def test_blocksparse_closed_form_and_invariants():
+    S, chunk, Hq, Hkv, D = 40, 8, 2, 1, 4
+    u = S // chunk
+    Q, K, V, dO = rand(S, Hq, Hkv, D, 16)
+    cm = _chunk_masks(u, 17)
+    # K == 0: uniform average over the allowed keys, LSE = log(their number)
+    O0, LSE0 = (lambda r: (r["O"], r["LSE"]))(definition.rows(Q, np.zeros_like(K), V, np.arange(S), 0.7,
+                                                                chunk=chunk, chunk_mask=cm))
+    allowed = np.kron(cm, np.ones((chunk, chunk), dtype=bool)) & np.tril(np.ones((S, S), dtype=bool))
+    cnt = allowed.sum(axis=1)
+    mean = (allowed[:, :, None, None] * V[None]).sum(axis=1) / cnt[:, None, None]
+    np.testing.assert_allclose(O0, np.repeat(mean, Hq, axis=1), atol=1e-14)
+    np.testing.assert_allclose(LSE0, np.tile(np.log(cnt), (Hq, 1)), atol=1e-14)
+    # rows of P still sum to one: sum_j dV_j = sum_i dO_i per KV head; a key chunk nobody but
+    # its own diagonal reads gets gradient only from its own chunk's rows
+    r = definition.attn_fwd_bwd(Q, K, V, dO, 0.7, chunk=chunk, chunk_mask=cm)
+    np.testing.assert_allclose(r["dV"].sum(axis=0)[0], dO.sum(axis=(0, 1)), atol=1e-12)
+    lonely = [j for j in range(u) if not cm[j + 1:, j].any()]
+    assert lonely
+    j = lonely[0]
+    rows_j = np.arange(j * chunk, (j + 1) * chunk)
+    Q2, dO2 = Q.copy(), dO.copy()
+    other = np.setdiff1d(np.arange(S), rows_j)
+    Q2[other] += 1.0
+    dO2[other] *= -3.0
+    r2 = definition.attn_fwd_bwd(Q2, K, V, dO2, 0.7, chunk=chunk, chunk_mask=cm)
+    np.testing.assert_array_equal(r["dK"][rows_j], r2["dK"][rows_j])
+    np.testing.assert_array_equal(r["dV"][rows_j], r2["dV"][rows_j])
+
+
+def test_blocksparse_oracle_rejects_bad_masks():
+    Q, K, V, dO = rand(16, 1, 1, 4, 18)
+    bad = np.ones((4, 4))
+    bad[2, 2] = 0  # a dropped diagonal entry would leave rows without any key
+    with pytest.raises(ValueError):
+        definition.rows(Q, K, V, np.arange(16), 1.0, chunk=4, chunk_mask=bad)
+    with pytest.raises(AssertionError):
+        definition.rows(Q, K, V, np.arange(16), 1.0, chunk=5, chunk_mask=np.ones((3, 3)))
