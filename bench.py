@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--seq", type=int, default=0, help="override the workload's sequence length")
     ap.add_argument("--offload", choices=["none", "kv", "kv+act"], default=None,
                     help="override which tensors live in pinned host memory")
+    ap.add_argument("--keep", type=float, default=None,
+                    help="block-sparse attention (Sec. 5.5): keep each below-diagonal chunk pair "
+                         "with this probability (seeded), always keep the diagonal")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-link-probe", action="store_true")
     ap.add_argument("--resident-compare", action="store_true",
@@ -124,7 +127,19 @@ def main():
     seed = 2024
     Q, K, V, dO = inputs.make_qkvdo(cfg.S, cfg.Hq, cfg.Hkv, cfg.D, cfg.dtype, seed, device="cuda")
     flags = (B.FPDT_KV_ON_HOST if cfg.kv_on_host else 0) | (B.FPDT_ACT_ON_HOST if cfg.act_on_host else 0)
-    bufs = runner.make_buffers(Q, K, V, dO, cfg.chunk, cfg.scale, flags)
+    mask = None
+    pair_frac = 1.0  # kept share of the dense causal FLOPs
+    if args.keep is not None:
+        import numpy as np
+        u = cfg.S // cfg.chunk
+        mask = np.tril(np.random.default_rng(7).random((u, u)) < args.keep)
+        np.fill_diagonal(mask, True)
+        C = float(cfg.chunk)
+        kept = (mask.sum() - u) * C * C + u * C * (C + 1) / 2
+        pair_frac = kept / (cfg.S * (cfg.S + 1) / 2.0)
+        cfg = __import__("dataclasses").replace(cfg, name="%s[keep=%g: %d of %d pairs]" % (
+            cfg.name, args.keep, int(mask.sum()), u * (u + 1) // 2))
+    bufs = runner.make_buffers(Q, K, V, dO, cfg.chunk, cfg.scale, flags, chunk_mask=mask)
     if cfg.kv_on_host:
         Kdev, Vdev = K, V
     del Q, dO
@@ -178,15 +193,15 @@ def main():
         prof[name] = {"total_ms": ms, "launches": n}
 
     ms_per_step = total_s * 1e3 / args.steps
-    flops_step = cfg.flops_fwd_bwd()
+    flops_step = cfg.flops_fwd_bwd() * pair_frac
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
-    fwd_flops = cfg.flops_fwd()
+    fwd_flops = cfg.flops_fwd() * pair_frac
 
     # dominant kernel: the one with the largest summed duration.  Algorithmic FLOPs of a
     # kernel = 2*D*Hq*S(S+1)/2 per GEMM it is defined by (forward 2, dK/dV 4, dQ 3).
     gemms = {"fwd_sweep": 2, "bwd_dkdv": 4, "bwd_dq": 3}
     dom = max(gemms, key=lambda k: prof[k]["total_ms"])
-    per_gemm = 2.0 * cfg.D * cfg.Hq * cfg.S * (cfg.S + 1) / 2.0
+    per_gemm = 2.0 * cfg.D * cfg.Hq * cfg.S * (cfg.S + 1) / 2.0 * pair_frac
     dom_flops = gemms[dom] * per_gemm * args.steps
     achieved = dom_flops / (prof[dom]["total_ms"] * 1e-3) / 1e12 if prof[dom]["total_ms"] > 0 else 0.0
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
@@ -230,7 +245,7 @@ def main():
                                                      B.FPDT_DTYPE_BF16, B.FPDT_PAIRWISE, False),
                             ws_bwd=B.alloc_workspace(cfg.S, cfg.chunk, cfg.Hq, cfg.Hkv, cfg.D,
                                                      B.FPDT_DTYPE_BF16, B.FPDT_PAIRWISE, True),
-                            chunk=cfg.chunk, scale=cfg.scale, flags=B.FPDT_PAIRWISE)
+                            chunk=cfg.chunk, scale=cfg.scale, flags=B.FPDT_PAIRWISE, chunk_mask=mask)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         runner.forward(b2)

@@ -138,6 +138,30 @@ int fpdt_attn_bwd(const void *Q, const void *K, const void *V, const void *O, co
                   size_t workspace_bytes, void *stream);
 
 /*
+ * Block-sparse variants (Sec. 5.5: with block-sparse attention only part of the key/value
+ * chunks is fetched from host memory, the queries are always the whole sequence).
+ * chunk_mask: u x u bytes in HOST memory (u = S / chunk), row = query chunk m, column = key
+ * chunk i; query chunk m attends key chunk i iff i <= m and chunk_mask[m * u + i] != 0
+ * (entries with i > m are ignored).  Pairs that are switched off are neither fetched nor
+ * computed; inside the pairs that are kept the arithmetic is that of fpdt_attn_fwd /
+ * fpdt_attn_bwd, so an all-ones mask gives the same bits as those with FPDT_PAIRWISE.
+ * The mask is read before the call returns.  Every diagonal entry must be set (a query row
+ * always keeps its own key): FPDT_ERR_INVALID_ARG otherwise.  The schedule is pair by pair:
+ * size the workspace with fpdt_attn_workspace_bytes(..., flags | FPDT_PAIRWISE, ...).
+ * All other arguments, layouts and errors as in fpdt_attn_fwd / fpdt_attn_bwd; the backward
+ * must be given the same mask as the forward that produced O and LSE.
+ */
+int fpdt_attn_fwd_blocksparse(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                              int64_t S, int64_t chunk, int Hq, int Hkv, int D, float scale,
+                              int dtype, unsigned flags, const unsigned char *chunk_mask,
+                              void *workspace, size_t workspace_bytes, void *stream);
+int fpdt_attn_bwd_blocksparse(const void *Q, const void *K, const void *V, const void *O,
+                              const float *LSE, const void *dO, void *dQ, void *dK, void *dV,
+                              int64_t S, int64_t chunk, int Hq, int Hkv, int D, float scale,
+                              int dtype, unsigned flags, const unsigned char *chunk_mask,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Online-softmax merge of two partial attention results over disjoint key sets
  * (the rescale of an intermediate result when a further chunk is folded in,
  * Sec. 4.1): LSE = logaddexp(LSE_a, LSE_b),

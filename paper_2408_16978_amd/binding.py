@@ -51,6 +51,10 @@ def load():
     L.fpdt_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, ci, ci, ci, cf, ci, cu, vp, sz, vp]
     L.fpdt_attn_bwd.restype = ci
     L.fpdt_attn_bwd.argtypes = [vp] * 9 + [i64, i64, ci, ci, ci, cf, ci, cu, vp, sz, vp]
+    L.fpdt_attn_fwd_blocksparse.restype = ci
+    L.fpdt_attn_fwd_blocksparse.argtypes = [vp, vp, vp, vp, vp, i64, i64, ci, ci, ci, cf, ci, cu, vp, vp, sz, vp]
+    L.fpdt_attn_bwd_blocksparse.restype = ci
+    L.fpdt_attn_bwd_blocksparse.argtypes = [vp] * 9 + [i64, i64, ci, ci, ci, cf, ci, cu, vp, vp, sz, vp]
     L.fpdt_attn_merge.restype = ci
     L.fpdt_attn_merge.argtypes = [vp] * 6 + [i64, ci, ci, ci, vp]
     L.fpdt_last_link_bytes.restype = ci
@@ -149,6 +153,43 @@ def fpdt_attn_bwd(Q, K, V, O, LSE, dO, dQ, dK, dV, chunk, scale, flags=0, worksp
     st = load().fpdt_attn_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO), _ptr(dQ),
                               _ptr(dK), _ptr(dV), S, chunk, Hq, Hkv, D, float(scale),
                               _dtype_code(Q), flags, ws_ptr, ws_bytes, _stream_handle(stream))
+    _check(st)
+
+
+def _mask_bytes(chunk_mask, u):
+    """u*u bytes (row = query chunk) from any array-like / tensor; kept alive by the caller."""
+    m = torch.as_tensor(chunk_mask).to("cpu")
+    if tuple(m.shape) != (u, u):
+        raise ValueError("chunk_mask must be [%d, %d], got %s" % (u, u, tuple(m.shape)))
+    return (m != 0).to(torch.uint8).contiguous()
+
+
+def fpdt_attn_fwd_blocksparse(Q, K, V, O, LSE, chunk, scale, chunk_mask, flags=0, workspace=None,
+                              stream=None):
+    """Forward with a [u, u] chunk mask (query chunk m reads key chunk i <= m iff mask[m, i])."""
+    S, Hq, D = Q.shape
+    Hkv = K.shape[1]
+    m = _mask_bytes(chunk_mask, S // chunk)
+    ws_ptr = _ptr(workspace)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().fpdt_attn_fwd_blocksparse(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), S, chunk, Hq,
+                                          Hkv, D, float(scale), _dtype_code(Q), flags, m.data_ptr(),
+                                          ws_ptr, ws_bytes, _stream_handle(stream))
+    _check(st)
+
+
+def fpdt_attn_bwd_blocksparse(Q, K, V, O, LSE, dO, dQ, dK, dV, chunk, scale, chunk_mask, flags=0,
+                              workspace=None, stream=None):
+    """Backward with the chunk mask the forward was given."""
+    S, Hq, D = Q.shape
+    Hkv = K.shape[1]
+    m = _mask_bytes(chunk_mask, S // chunk)
+    ws_ptr = _ptr(workspace)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().fpdt_attn_bwd_blocksparse(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO),
+                                          _ptr(dQ), _ptr(dK), _ptr(dV), S, chunk, Hq, Hkv, D,
+                                          float(scale), _dtype_code(Q), flags, m.data_ptr(), ws_ptr,
+                                          ws_bytes, _stream_handle(stream))
     _check(st)
 
 

@@ -62,7 +62,24 @@ struct Problem {
     }
     size_t q_chunk_bytes() const { return (size_t)C * Hq * D * esize(); }
     size_t kv_chunk_bytes() const { return (size_t)C * Hkv * D * esize(); }
+    // Block-sparse variant (Sec. 5.5): u x u bytes, row = query chunk, column = key chunk; empty =
+    // dense.  The diagonal is always set (checked on entry).
+    std::vector<unsigned char> mask;
+    bool on(int64_t m, int64_t i) const { return mask.empty() || mask[(size_t)(m * u + i)] != 0; }
+    int64_t first_key_chunk(int64_t m) const { int64_t i = 0; while (!on(m, i)) ++i; return i; }
+    int64_t last_query_chunk(int64_t j) const { int64_t i = u - 1; while (!on(i, j)) --i; return i; }
 };
+
+// Copy and check a caller's chunk mask (host memory, read before the entry point returns).
+int take_mask(Problem& p, const unsigned char* chunk_mask)
+{
+    if (!chunk_mask) return fail(FPDT_ERR_INVALID_ARG, "NULL chunk mask");
+    p.mask.assign(chunk_mask, chunk_mask + (size_t)(p.u * p.u));
+    for (int64_t m = 0; m < p.u; ++m)
+        if (!p.mask[(size_t)(m * p.u + m)])
+            return fail(FPDT_ERR_INVALID_ARG, "chunk mask drops the diagonal pair (%lld, %lld): its query rows would have no key", (long long)m, (long long)m);
+    return FPDT_OK;
+}
 
 // Scalar validation: touches no GPU.
 int validate_scalars(Problem& p, int64_t S, int64_t chunk, int Hq, int Hkv, int D, float scale,
@@ -330,6 +347,7 @@ int fwd_f32(const Problem& p, const float* Q, const float* K, const float* V, fl
 {
     for (int64_t m = 0; m < p.u; ++m)
         for (int64_t i = 0; i <= m; ++i) {
+            if (!p.on(m, i)) continue;
             F32FwdArgs a;
             a.Q = Q + (size_t)m * p.C * p.Hq * p.D;
             a.K = K + (size_t)i * p.C * p.Hkv * p.D;
@@ -340,7 +358,7 @@ int fwd_f32(const Problem& p, const float* Q, const float* K, const float* V, fl
             a.st_acc = f.st_acc; a.st_ml = f.st_ml;
             a.q_pos0 = m * p.C; a.k_pos0 = i * p.C; a.n_q = p.C; a.n_k = p.C;
             a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
-            a.flags = (i == 0 ? SWEEP_INIT : 0) | (i == m ? SWEEP_FINAL : 0);
+            a.flags = (i == p.first_key_chunk(m) ? SWEEP_INIT : 0) | (i == m ? SWEEP_FINAL : 0);
             launch_f32_fwd_pair(a, st);
         }
     return launch_status("fp32 forward");
@@ -379,7 +397,8 @@ int fwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
     // the K/V fetch sequence is the pair sequence
     std::vector<int64_t> kv_seq;
     for (int64_t m = 0; m < p.u; ++m)
-        for (int64_t i = 0; i <= m; ++i) kv_seq.push_back(i);
+        for (int64_t i = 0; i <= m; ++i)
+            if (p.on(m, i)) kv_seq.push_back(i);
     auto fetch_kv = [&](size_t t) -> int {
         const int b = (int)(t & 1);
         HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_KV_FREE0 + b], 0));
@@ -413,7 +432,8 @@ int fwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
             LSEm = f.lse_buf[qbuf];
             lse_stride = p.C;
         }
-        for (int64_t i = 0; i <= m; ++i, ++t) {
+        for (int64_t i = 0; i <= m; ++i) {
+            if (!p.on(m, i)) continue;  // neither fetched nor computed
             const char* Ki = K + (size_t)i * kvb;
             const char* Vi = V + (size_t)i * kvb;
             if (kvh) {
@@ -434,8 +454,9 @@ int fwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
             a.st_acc = f.st_acc; a.st_ml = f.st_ml;
             a.q_pos0 = m * p.C; a.k_pos0 = i * p.C; a.n_q = p.C; a.n_keys = p.C;
             a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
-            a.flags = (i == 0 ? SWEEP_INIT : 0) | (i == m ? SWEEP_FINAL : 0);
+            a.flags = (i == p.first_key_chunk(m) ? SWEEP_INIT : 0) | (i == m ? SWEEP_FINAL : 0);
             { PROF(FPDT_PROF_FWD, st); launch_fwd_sweep(a, st); }
+            ++t;
         }
         if (acth) {
             HIP_TRY(hipEventRecord(c->ev[EV_ACT_FREE0 + qbuf], st));
@@ -484,10 +505,12 @@ int bwd_f32(const Problem& p, const float* Q, const float* K, const float* V, co
     };
     if (p.q_outer()) {
         for (int64_t i = 0; i < p.u; ++i)
-            for (int64_t j = 0; j <= i; ++j) pair(i, j);
+            for (int64_t j = 0; j <= i; ++j)
+                if (p.on(i, j)) pair(i, j);
     } else {
         for (int64_t j = 0; j < p.u; ++j)
-            for (int64_t i = j; i < p.u; ++i) pair(i, j);
+            for (int64_t i = j; i < p.u; ++i)
+                if (p.on(i, j)) pair(i, j);
     }
     return launch_status("fp32 backward");
 }
@@ -543,10 +566,12 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
     std::vector<std::pair<int64_t, int64_t>> pairs;  // (i = query chunk, j = key chunk)
     if (qo) {
         for (int64_t i = 0; i < p.u; ++i)
-            for (int64_t j = 0; j <= i; ++j) pairs.push_back({i, j});
+            for (int64_t j = 0; j <= i; ++j)
+                if (p.on(i, j)) pairs.push_back({i, j});
     } else {
         for (int64_t j = 0; j < p.u; ++j)
-            for (int64_t i = j; i < p.u; ++i) pairs.push_back({i, j});
+            for (int64_t i = j; i < p.u; ++i)
+                if (p.on(i, j)) pairs.push_back({i, j});
     }
     // K/V fetch sequence: one fetch whenever the key chunk changes
     std::vector<int64_t> kv_seq;
@@ -585,9 +610,12 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
     int64_t stat_stride = p.S;
     for (size_t t = 0; t < pairs.size(); ++t) {
         const int64_t i = pairs[t].first, j = pairs[t].second;
-        const bool last_for_q = (j == i);                     // both orders end chunk i's dQ at j == i
-        const bool last_for_kv = (i == p.u - 1);              // and chunk j's dK/dV at i == u-1
-        const bool first_for_q = (j == 0), first_for_kv = (i == j);
+        // both orders visit the key chunks of a query chunk, and the query chunks of a key chunk,
+        // in ascending order: dQ_i starts at its first kept key chunk and ends on the diagonal,
+        // dK_j / dV_j start on the diagonal and end at the last query chunk that keeps chunk j
+        const bool last_for_q = (j == i);
+        const bool last_for_kv = (i == p.last_query_chunk(j));
+        const bool first_for_q = (j == p.first_key_chunk(i)), first_for_kv = (i == j);
         // ---- key/value side ----
         if (j != cur_j) {
             if (kvh) {
@@ -632,7 +660,10 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
             launch_pack(dOi, p.C, p.Hq, p.D, f.dOnat, f.dOtr, p.C / 32, st);
             cur_i = i;
         }
-        if (t == 0)  // pair (0, 0): the head of the sequence gets its cancellation-safe Delta
+        // Rows that see only a few keys get their cancellation-safe Delta: the head of the
+        // sequence (pair (0, 0)) and, with a chunk mask, the head of every query chunk that keeps
+        // no earlier key chunk (its diagonal pair is then the first pair that reads its Delta).
+        if (i == j && p.first_key_chunk(i) == i)
             launch_delta_head(Qi, dOi, Kj, Vj, LSEi, stat_stride, DELTA_HEAD_ROWS, p.Hq, p.Hkv, p.D,
                               p.scale, const_cast<float*>(Deltai), st);
         // ---- the pair ----
@@ -720,15 +751,17 @@ int64_t fpdt_attn_pick_chunk(int64_t S, int Hq, int Hkv, int D, int dtype, unsig
     return 0;
 }
 
-int fpdt_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int64_t S,
-                  int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype, unsigned flags,
-                  void* workspace, size_t workspace_bytes, void* stream)
+static int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, float* LSE, int64_t S,
+                         int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype, unsigned flags,
+                         const unsigned char* chunk_mask, bool sparse, void* workspace,
+                         size_t workspace_bytes, void* stream)
 {
     g_err.clear();
     g_h2d_bytes = g_d2h_bytes = 0;
     if (!Q || !K || !V || !O || !LSE) return fail(FPDT_ERR_INVALID_ARG, "NULL tensor pointer");
     Problem p;
     TRY(validate_scalars(p, S, chunk, Hq, Hkv, D, scale, dtype, flags));
+    if (sparse) TRY(take_mask(p, chunk_mask));
     const size_t need = plan_fwd(p, nullptr).total;
     if (need && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256))
         TRY(check_workspace(workspace, workspace_bytes, need));
@@ -748,10 +781,28 @@ int fpdt_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* L
     return fwd_bf16_pairs(p, (const char*)Q, (const char*)K, (const char*)V, (char*)O, LSE, f, st);
 }
 
-int fpdt_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
-                  const void* dO, void* dQ, void* dK, void* dV, int64_t S, int64_t chunk, int Hq,
-                  int Hkv, int D, float scale, int dtype, unsigned flags, void* workspace,
-                  size_t workspace_bytes, void* stream)
+int fpdt_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int64_t S,
+                  int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype, unsigned flags,
+                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    return attn_fwd_impl(Q, K, V, O, LSE, S, chunk, Hq, Hkv, D, scale, dtype, flags, nullptr, false,
+                         workspace, workspace_bytes, stream);
+}
+
+int fpdt_attn_fwd_blocksparse(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                              int64_t S, int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype,
+                              unsigned flags, const unsigned char* chunk_mask, void* workspace,
+                              size_t workspace_bytes, void* stream)
+{
+    return attn_fwd_impl(Q, K, V, O, LSE, S, chunk, Hq, Hkv, D, scale, dtype, flags | FPDT_PAIRWISE,
+                         chunk_mask, true, workspace, workspace_bytes, stream);
+}
+
+static int attn_bwd_impl(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                         const void* dO, void* dQ, void* dK, void* dV, int64_t S, int64_t chunk, int Hq,
+                         int Hkv, int D, float scale, int dtype, unsigned flags,
+                         const unsigned char* chunk_mask, bool sparse, void* workspace,
+                         size_t workspace_bytes, void* stream)
 {
     g_err.clear();
     g_h2d_bytes = g_d2h_bytes = 0;
@@ -759,6 +810,7 @@ int fpdt_attn_bwd(const void* Q, const void* K, const void* V, const void* O, co
         return fail(FPDT_ERR_INVALID_ARG, "NULL tensor pointer");
     Problem p;
     TRY(validate_scalars(p, S, chunk, Hq, Hkv, D, scale, dtype, flags));
+    if (sparse) TRY(take_mask(p, chunk_mask));
     const size_t need = plan_bwd(p, nullptr).total;
     if (need && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256))
         TRY(check_workspace(workspace, workspace_bytes, need));
@@ -782,6 +834,25 @@ int fpdt_attn_bwd(const void* Q, const void* K, const void* V, const void* O, co
     if (p.fused()) return bwd_bf16_fused(p, Q, K, V, O, LSE, dO, dQ, dK, dV, f, st);
     return bwd_bf16_pairs(p, (const char*)Q, (const char*)K, (const char*)V, (const char*)O, LSE,
                           (const char*)dO, (char*)dQ, (char*)dK, (char*)dV, f, st);
+}
+
+int fpdt_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                  const void* dO, void* dQ, void* dK, void* dV, int64_t S, int64_t chunk, int Hq,
+                  int Hkv, int D, float scale, int dtype, unsigned flags, void* workspace,
+                  size_t workspace_bytes, void* stream)
+{
+    return attn_bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, S, chunk, Hq, Hkv, D, scale, dtype, flags,
+                         nullptr, false, workspace, workspace_bytes, stream);
+}
+
+int fpdt_attn_bwd_blocksparse(const void* Q, const void* K, const void* V, const void* O,
+                              const float* LSE, const void* dO, void* dQ, void* dK, void* dV, int64_t S,
+                              int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype,
+                              unsigned flags, const unsigned char* chunk_mask, void* workspace,
+                              size_t workspace_bytes, void* stream)
+{
+    return attn_bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, S, chunk, Hq, Hkv, D, scale, dtype,
+                         flags | FPDT_PAIRWISE, chunk_mask, true, workspace, workspace_bytes, stream);
 }
 
 int fpdt_attn_merge(const void* O_a, const float* LSE_a, const void* O_b, const float* LSE_b,

@@ -41,10 +41,14 @@ class Buffers:
     chunk: int
     scale: float
     flags: int
+    chunk_mask: object = None  # [u, u] block-sparse mask, or None for dense attention
 
 
-def make_buffers(Q, K, V, dO, chunk, scale, flags=0, bwd=True) -> Buffers:
-    """Place inputs per the offload flags and allocate outputs + workspaces."""
+def make_buffers(Q, K, V, dO, chunk, scale, flags=0, bwd=True, chunk_mask=None) -> Buffers:
+    """Place inputs per the offload flags and allocate outputs + workspaces.  With a chunk mask
+    the block-sparse entry points are used (pair-by-pair schedule)."""
+    if chunk_mask is not None:
+        flags |= B.FPDT_PAIRWISE
     S, Hq, D = Q.shape
     Hkv = K.shape[1]
     kvh = bool(flags & B.FPDT_KV_ON_HOST)
@@ -60,15 +64,23 @@ def make_buffers(Q, K, V, dO, chunk, scale, flags=0, bwd=True) -> Buffers:
         dV=_empty_like_placed((S, Hkv, D), Q.dtype, kvh) if bwd else None,
         ws_fwd=B.alloc_workspace(S, chunk, Hq, Hkv, D, dt, fwd_flags, False),
         ws_bwd=B.alloc_workspace(S, chunk, Hq, Hkv, D, dt, flags, True) if bwd else None,
-        chunk=chunk, scale=scale, flags=flags)
+        chunk=chunk, scale=scale, flags=flags, chunk_mask=chunk_mask)
     return bufs
 
 
 def forward(b: Buffers, stream=None):
     fwd_flags = b.flags & ~(B.FPDT_BWD_KV_OUTER | B.FPDT_BWD_Q_OUTER)
-    B.fpdt_attn_fwd(b.Q, b.K, b.V, b.O, b.LSE, b.chunk, b.scale, fwd_flags, b.ws_fwd, stream)
+    if b.chunk_mask is not None:
+        B.fpdt_attn_fwd_blocksparse(b.Q, b.K, b.V, b.O, b.LSE, b.chunk, b.scale, b.chunk_mask,
+                                    fwd_flags, b.ws_fwd, stream)
+    else:
+        B.fpdt_attn_fwd(b.Q, b.K, b.V, b.O, b.LSE, b.chunk, b.scale, fwd_flags, b.ws_fwd, stream)
 
 
 def backward(b: Buffers, stream=None):
-    B.fpdt_attn_bwd(b.Q, b.K, b.V, b.O, b.LSE, b.dO, b.dQ, b.dK, b.dV, b.chunk, b.scale, b.flags,
-                    b.ws_bwd, stream)
+    if b.chunk_mask is not None:
+        B.fpdt_attn_bwd_blocksparse(b.Q, b.K, b.V, b.O, b.LSE, b.dO, b.dQ, b.dK, b.dV, b.chunk,
+                                    b.scale, b.chunk_mask, b.flags, b.ws_bwd, stream)
+    else:
+        B.fpdt_attn_bwd(b.Q, b.K, b.V, b.O, b.LSE, b.dO, b.dQ, b.dK, b.dV, b.chunk, b.scale, b.flags,
+                        b.ws_bwd, stream)
