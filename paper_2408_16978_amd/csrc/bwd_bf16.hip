@@ -80,7 +80,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
     static_assert(RING == 2, "the step loop below alternates between two slots");
     __shared__ u32x4 slot0[SLOT_U4], slot1[SLOT_U4];
     __shared__ u32x4 vst[NWAVE * DT * 64];  // V NAT fragments of the workgroup's keys
-    __shared__ float stat0[64], stat1[64];  // [0,32): LSE*log2e, [32,64): Delta of the staged block
+    __shared__ __attribute__((aligned(16))) float stat0[64], stat1[64];  // [0,32): LSE*log2e, [32,64): -Delta of the staged block
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wu = __builtin_amdgcn_readfirstlane(w);
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
 
     if (n_iter > 0) {
         issue(0, slot0);
-        if (tid < 64) stat0[tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
+        if (tid < 64) stat0[tid] = tid < 32 ? pre_stat * LOG2E : -pre_stat;
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -198,13 +198,21 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
                     dv[db] = mfma32(as_bf16x8(ot[(1 * DB + db) * 64 + lane]), pf1, dv[db]);
                 }
             }
-            // dP = dO V^T, dS = p (dP - Delta)
+            // dP - Delta = dO V^T - Delta: the chain starts from the tile of -Delta (registers
+            // 4a .. 4a+3 hold rows 8a + 4 half + 0..3: four 16-byte reads) instead of zero, which
+            // saves a subtraction per element; dS = p (dP - Delta)
             floatx16 dp;
 #pragma unroll
-            for (int t = 0; t < DT; ++t)
-                dp = mfma32(as_bf16x8(on[t * 64 + lane]), as_bf16x8(vmine[t * 64 + lane]), t == 0 ? zero : dp);
+            for (int a4 = 0; a4 < 4; ++a4) {
+                const floatx4 nd = *reinterpret_cast<const floatx4*>(st + 32 + 8 * a4 + 4 * half);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) dp[r] = s[r] * (dp[r] - st[32 + 8 * (r >> 2) + 4 * half + (r & 3)]);
+                for (int b = 0; b < 4; ++b) dp[4 * a4 + b] = nd[b];
+            }
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+                dp = mfma32(as_bf16x8(on[t * 64 + lane]), as_bf16x8(vmine[t * 64 + lane]), dp);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dp[r] = s[r] * dp[r];
             const bf16x8 df0 = pack_half<0>(dp), df1 = pack_half<1>(dp);
             // dK^T += Q^T dS
 #pragma unroll
@@ -213,7 +221,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
                 dk[db] = mfma32(as_bf16x8(qt[(1 * DB + db) * 64 + lane]), df1, dk[db]);
             }
         }
-        if (more && tid < 64) nst[tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
+        if (more && tid < 64) nst[tid] = tid < 32 ? pre_stat * LOG2E : -pre_stat;
         wait_vmem_at_most<0>();  // the direct-to-LDS loads of step it+1 have landed
         barrier_no_fence();
     };
@@ -251,6 +259,8 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
 // with the dS arithmetic in their shadow | dK MFMAs.
 #define FPDT_MFMA_V0(d, a, b) \
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b))
+#define FPDT_MFMA_VC(d, a, b, c) \
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(d) : "v"(a), "v"(b), "v"(c))
 #define FPDT_MFMA_V(d, a, b) \
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b))
 #define FPDT_MFMA_A(d, a, b) \
@@ -272,7 +282,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     static_assert(RING == 2, "the step loops below alternate between two slots");
     __shared__ u32x4 slot0[SLOT_U4], slot1[SLOT_U4];
     __shared__ u32x4 vst[NW * NK * DT * 64];  // V NAT fragments of the workgroup's keys
-    __shared__ float stat0[64], stat1[64];
+    __shared__ __attribute__((aligned(16))) float stat0[64], stat1[64];  // LSE*log2e | -Delta
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wu = __builtin_amdgcn_readfirstlane(w);
@@ -385,6 +395,16 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
             auto stat2 = [&](int base, int r) {  // rows r, r+1 (r even): consecutive floats
                 return *reinterpret_cast<const float2*>(st + base + 8 * (r >> 2) + 4 * half + (r & 3));
             };
+            // The dP chains start from the tile of -Delta instead of zero (registers 4a .. 4a+3
+            // hold rows 8a + 4 half + 0..3: four 16-byte reads), so the MFMAs deliver dP - Delta
+            // and the dS arithmetic loses its subtraction.
+            floatx16 nd;
+#pragma unroll
+            for (int a4 = 0; a4 < 4; ++a4) {
+                const floatx4 q4 = *reinterpret_cast<const floatx4*>(st + 32 + 8 * a4 + 4 * half);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) nd[4 * a4 + b] = q4[b];
+            }
             float2 stat_nx = stat2(0, 0);
             // ---- A: S = Q K^T, two chains ----
 #pragma unroll
@@ -400,15 +420,15 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                 fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
                 FPDT_SCHED_FENCE();
             }
-            // ---- B: dP = dO V^T, exp of S in the shadow of the MFMAs ----
+            // ---- B: dP - Delta = dO V^T - Delta, exp of S in the shadow of the MFMAs ----
 #pragma unroll
             for (int t = 0; t < DT; ++t) {
                 const int u = DT + t;
                 const float2 lse = stat_nx;
-                stat_nx = t + 1 < DT ? stat2(0, 2 * t + 2) : stat2(32, 0);
+                if (t + 1 < DT) stat_nx = stat2(0, 2 * t + 2);
                 if (t == 0) {
-                    FPDT_MFMA_V0(dp0, fr[u % 6], vb0[t % 3]);
-                    FPDT_MFMA_V0(dp1, fr[u % 6], vb1[t % 3]);
+                    FPDT_MFMA_VC(dp0, fr[u % 6], vb0[t % 3], nd);
+                    FPDT_MFMA_VC(dp1, fr[u % 6], vb1[t % 3], nd);
                     FPDT_MFMA_TO_VALU_NOPS();  // s0, s1 are complete and readable from here on
                 } else {
                     FPDT_MFMA_V(dp0, fr[u % 6], vb0[t % 3]);
@@ -442,13 +462,11 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
             pf[0][1] = pack_half<1>(s0);
             pf[1][1] = pack_half<1>(s1);
             FPDT_SCHED_FENCE();
-            // ---- C: dV^T += dO^T p, dS = p (dP - Delta) in the shadow ----
+            // ---- C: dV^T += dO^T p, dS = p (dP - Delta) in the shadow (dp holds dP - Delta) ----
 #pragma unroll
             for (int i = 0; i < 2 * DB; ++i) {
                 const int u = 2 * DT + i;
                 const int s2 = i / DB, db = i % DB;
-                const float2 dl = stat_nx;
-                if (i + 1 < 2 * DB) stat_nx = stat2(32, 2 * i + 2);
                 FPDT_MFMA_A(dv[0][db], fr[u % 6], pf[0][s2]);
                 FPDT_MFMA_A(dv[1][db], fr[u % 6], pf[1][s2]);
                 if (i == 0) FPDT_MFMA_TO_VALU_NOPS();  // dp0, dp1 readable
@@ -456,9 +474,8 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                 FPDT_SCHED_FENCE();
 #pragma unroll
                 for (int r = 2 * i; r < 2 * i + 2; ++r) {
-                    const float dlt = (r & 1) ? dl.y : dl.x;
-                    dp0[r] = s0[r] * (dp0[r] - dlt);
-                    dp1[r] = s1[r] * (dp1[r] - dlt);
+                    dp0[r] = s0[r] * dp0[r];
+                    dp1[r] = s1[r] * dp1[r];
                 }
                 if (i == 3) {
                     df[0][0] = pack_half<0>(dp0);
@@ -481,14 +498,14 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
             }
 #undef FPDT_AFRAG
         }
-        if (more && tid < 64) nst[tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
+        if (more && tid < 64) nst[tid] = tid < 32 ? pre_stat * LOG2E : -pre_stat;
         wait_vmem_at_most<0>();  // the direct-to-LDS loads of step it+1 have landed
         barrier_no_fence();
     };
 
     if (n_iter > 0) {
         issue(0, slot0);
-        if (tid < 64) stat0[tid] = tid < 32 ? pre_stat * LOG2E : pre_stat;
+        if (tid < 64) stat0[tid] = tid < 32 ? pre_stat * LOG2E : -pre_stat;
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -597,7 +614,18 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
         }
     }
     const float lse2 = p.LSE[(size_t)head * p.row_stat_stride + row] * LOG2E;
-    const float delta = p.Delta[(size_t)head * p.row_stat_stride + row];
+    // The dP chain starts from -Delta instead of zero, so the MFMAs deliver dP - Delta directly
+    // (one vector instruction per element less; plain vector instructions take issue slots from
+    // the MFMAs of the SIMD's other wave).  The same trick for the scores would need Q held
+    // pre-multiplied by scale * log2(e) in bf16: measured, that rounding alone pushes dQ past its
+    // error budget (the cancellation in p (dP - Delta) amplifies it), so the scores keep their
+    // fp32 multiply-add.
+    floatx16 neg_delta;
+    {
+        const float dl = -p.Delta[(size_t)head * p.row_stat_stride + row];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) neg_delta[r] = dl;
+    }
 
     floatx16 acc[DB];
     const size_t wg = blockIdx.x;
@@ -630,23 +658,28 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
         for (int kb = 0; kb < KB; ++kb) {
             const int64_t key0 = p.k_pos0 + (int64_t)it * BK + 32 * kb;
             if (key0 <= qpos_last) {  // wave-uniform
-                // all NAT fragments of the block are requested before the MFMA chains start, the
-                // TR fragments right after them: they arrive under the chains / the arithmetic
-                bf16x8 kfr[DT], vfr[DT];
+                // K fragments first; the V fragments are requested one per score MFMA (each has
+                // the rest of the chain in front of its first use), the K-TR fragments after the
+                // dP chain: they arrive under the exp2 / multiply arithmetic.  No more than two
+                // fragment sets are live at a time.
+                bf16x8 kfr[DT], vfr[DT], tfr[2][DB];
 #pragma unroll
-                for (int t = 0; t < DT; ++t) {
-                    kfr[t] = as_bf16x8(kn[(kb * DT + t) * 64 + lane]);
-                    vfr[t] = as_bf16x8(vn[(kb * DT + t) * 64 + lane]);
-                }
+                for (int t = 0; t < DT; ++t) kfr[t] = as_bf16x8(kn[(kb * DT + t) * 64 + lane]);
                 floatx16 s, dp;
 #pragma unroll
                 for (int t = 0; t < DT; ++t) {
                     s = mfma32(kfr[t], qf[t], t == 0 ? zero : s);
-                    dp = mfma32(vfr[t], of[t], t == 0 ? zero : dp);
+                    vfr[t] = as_bf16x8(vn[(kb * DT + t) * 64 + lane]);
                 }
-                __builtin_amdgcn_sched_group_barrier(0x100, 2 * DT, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 2 * DT, 0);
-                bf16x8 tfr[2][DB];
+#pragma unroll
+                for (int t = 0; t < DT; ++t) dp = mfma32(vfr[t], of[t], t == 0 ? neg_delta : dp);
+                __builtin_amdgcn_sched_group_barrier(0x100, DT, 0);
+#pragma unroll
+                for (int t = 0; t < DT; ++t) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, DT, 0);
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
@@ -660,7 +693,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
                         if (key0 + 8 * (r >> 2) + 4 * half + (r & 3) > qpos) s[r] = 0.f;
                 }
 #pragma unroll
-                for (int r = 0; r < 16; ++r) dp[r] = s[r] * (dp[r] - delta);
+                for (int r = 0; r < 16; ++r) dp[r] = s[r] * dp[r];
                 const bf16x8 df0 = pack_half<0>(dp), df1 = pack_half<1>(dp);
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
