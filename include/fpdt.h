@@ -193,6 +193,23 @@ enum { FPDT_PROF_FWD = 0, FPDT_PROF_DKDV = 1, FPDT_PROF_DQ = 2, FPDT_PROF_H2D = 
 int fpdt_profile_enable(int on);
 int fpdt_profile_read(int kind, double *total_ms, int64_t *launches);
 
+/*
+ * Event-ordering checks for the offload pipeline (Sec. 4.2: copies on side streams, one buffer
+ * being filled while the other is used).  For tests of the pipeline itself, not for production:
+ *   FPDT_DEBUG_POISON_STAGING  every device staging buffer is filled with 0xFF bytes (NaNs)
+ *                              right before the host-to-device copy into it, on the copy's
+ *                              stream: a kernel that does not wait for the copy reads NaNs;
+ *   FPDT_DEBUG_DELAY_COPIES    a 48 MiB dummy copy is queued in front of every staged copy
+ *                              (either direction), so copies finish much later than they are
+ *                              enqueued: a missing wait shows up as stale or poisoned data,
+ *                              a missing buffer-release wait as a late overwrite.
+ * With either flag a correct pipeline still returns bit for bit what the resident run returns.
+ * flags = 0 switches both off.  The first call with FPDT_DEBUG_DELAY_COPIES allocates the dummy
+ * buffers (48 MiB pinned host + 48 MiB device per GPU, kept until the process ends).
+ */
+enum { FPDT_DEBUG_POISON_STAGING = 1u << 0, FPDT_DEBUG_DELAY_COPIES = 1u << 1 };
+int fpdt_debug_configure(unsigned flags);
+
 /* Text describing the calling thread's most recent error ("" if none). Never NULL. */
 const char *fpdt_last_error(void);
 

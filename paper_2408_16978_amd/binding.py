@@ -22,6 +22,7 @@ FPDT_BWD_Q_OUTER = 1 << 3
 FPDT_PAIRWISE = 1 << 4
 FPDT_CHUNK_MULTIPLE = 256
 FPDT_PROF_FWD, FPDT_PROF_DKDV, FPDT_PROF_DQ, FPDT_PROF_H2D, FPDT_PROF_D2H = range(5)
+FPDT_DEBUG_POISON_STAGING, FPDT_DEBUG_DELAY_COPIES = 1, 2
 
 _lib = None
 
@@ -63,6 +64,8 @@ def load():
     L.fpdt_profile_enable.argtypes = [ci]
     L.fpdt_profile_read.restype = ci
     L.fpdt_profile_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    L.fpdt_debug_configure.restype = ci
+    L.fpdt_debug_configure.argtypes = [cu]
     L.fpdt_last_error.restype = ctypes.c_char_p
     L.fpdt_version.restype = ctypes.c_char_p
     _lib = L
@@ -108,6 +111,11 @@ def fpdt_last_link_bytes():
     h, d = ctypes.c_uint64(0), ctypes.c_uint64(0)
     load().fpdt_last_link_bytes(ctypes.byref(h), ctypes.byref(d))
     return int(h.value), int(d.value)
+
+
+def fpdt_debug_configure(flags: int):
+    """Event-ordering checks of the offload pipeline (poisoned staging buffers, delayed copies)."""
+    _check(load().fpdt_debug_configure(flags))
 
 
 def fpdt_profile_enable(on: bool):

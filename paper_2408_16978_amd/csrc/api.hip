@@ -224,7 +224,13 @@ struct DeviceCtx {
     bool ready = false;
     hipStream_t h2d = nullptr, d2h = nullptr;
     hipEvent_t ev[EV_COUNT] = {};
+    // event-ordering checks (fpdt_debug_configure): a pinned / device buffer pair whose copy is
+    // queued in front of every staged copy to hold it back
+    void* delay_host = nullptr;
+    void* delay_dev = nullptr;
 };
+unsigned g_debug = 0;
+constexpr size_t DELAY_BYTES = (size_t)48 << 20;
 std::mutex g_mu;  // serialises enqueueing calls that use the shared side streams
 DeviceCtx g_ctx[64];
 
@@ -318,8 +324,33 @@ struct ProfScope {
 #define PROF(kind, st) ProfScope prof_scope_##__LINE__(kind, st)
 
 // H2D / D2H helpers that keep the link-byte counters.
+#define TRY(expr)                       \
+    do {                                \
+        int rc_ = (expr);               \
+        if (rc_ != FPDT_OK) return rc_; \
+    } while (0)
+
+// With FPDT_DEBUG_DELAY_COPIES every staged copy is held back by a large dummy copy on the same
+// stream; with FPDT_DEBUG_POISON_STAGING the destination of a host-to-device copy is first
+// filled with 0xFF bytes (bf16 / fp32 NaNs).  A consumer that does not wait for the copy's
+// event then reads NaNs, and a producer that does not wait for a buffer's release is
+// overwritten late: both show up as a mismatch against the resident run.
+int debug_hold_back(bool to_device, void* dst, size_t bytes, hipStream_t st)
+{
+    if (!g_debug) return FPDT_OK;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    DeviceCtx& c = g_ctx[dev];
+    if ((g_debug & FPDT_DEBUG_DELAY_COPIES) && c.delay_host)
+        HIP_TRY(hipMemcpyAsync(to_device ? c.delay_dev : c.delay_host, to_device ? c.delay_host : c.delay_dev,
+                               DELAY_BYTES, to_device ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost, st));
+    if ((g_debug & FPDT_DEBUG_POISON_STAGING) && to_device) launch_fill_bytes(dst, bytes, 0xFF, st);
+    return FPDT_OK;
+}
+
 int copy_h2d(void* dst, const void* src, size_t bytes, hipStream_t st)
 {
+    TRY(debug_hold_back(true, dst, bytes, st));
     PROF(FPDT_PROF_H2D, st);
     HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st));
     g_h2d_bytes += bytes;
@@ -327,17 +358,12 @@ int copy_h2d(void* dst, const void* src, size_t bytes, hipStream_t st)
 }
 int copy_d2h(void* dst, const void* src, size_t bytes, hipStream_t st)
 {
+    TRY(debug_hold_back(false, nullptr, 0, st));
     PROF(FPDT_PROF_D2H, st);
     HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, st));
     g_d2h_bytes += bytes;
     return FPDT_OK;
 }
-
-#define TRY(expr)                       \
-    do {                                \
-        int rc_ = (expr);               \
-        if (rc_ != FPDT_OK) return rc_; \
-    } while (0)
 
 // =========================================================================================
 // forward
@@ -910,6 +936,25 @@ int fpdt_profile_read(int kind, double* total_ms, int64_t* launches)
     g_prof.swap(keep);
     if (total_ms) *total_ms = ms;
     if (launches) *launches = n;
+    return FPDT_OK;
+}
+
+int fpdt_debug_configure(unsigned flags)
+{
+    g_err.clear();
+    if (flags & ~(unsigned)(FPDT_DEBUG_POISON_STAGING | FPDT_DEBUG_DELAY_COPIES))
+        return fail(FPDT_ERR_INVALID_ARG, "unknown debug flag bits 0x%x", flags);
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (flags & FPDT_DEBUG_DELAY_COPIES) {
+        DeviceCtx* c = nullptr;
+        TRY(get_ctx(&c));
+        if (!c->delay_host) {
+            HIP_TRY(hipHostMalloc(&c->delay_host, DELAY_BYTES, hipHostMallocDefault));
+            HIP_TRY(hipMalloc(&c->delay_dev, DELAY_BYTES));
+            memset(c->delay_host, 0, DELAY_BYTES);
+        }
+    }
+    g_debug = flags;
     return FPDT_OK;
 }
 

@@ -213,12 +213,12 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* Oa, const float* La
     if (sub == 0) Lo[(size_t)h * rows + row] = lse;
 }
 
-__global__ __launch_bounds__(256) void zero_kernel(uint4* p, size_t n16, unsigned char* tail, int ntail)
+__global__ __launch_bounds__(256) void fill_kernel(uint4* p, size_t n16, unsigned char* tail, int ntail, unsigned word)
 {
     const size_t i0 = (size_t)blockIdx.x * 256 + threadIdx.x;
     const size_t step = (size_t)gridDim.x * 256;
-    for (size_t i = i0; i < n16; i += step) p[i] = make_uint4(0, 0, 0, 0);
-    if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0;
+    for (size_t i = i0; i < n16; i += step) p[i] = make_uint4(word, word, word, word);
+    if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = (unsigned char)word;
 }
 
 }  // namespace
@@ -249,15 +249,18 @@ void launch_merge(const void* Oa, const float* La, const void* Ob, const float* 
                                                   (float*)Oo, Lo, rows, Hq, D);
 }
 
-void launch_zero(void* p, size_t bytes, hipStream_t st)
+void launch_zero(void* p, size_t bytes, hipStream_t st) { launch_fill_bytes(p, bytes, 0x00, st); }
+
+void launch_fill_bytes(void* p, size_t bytes, unsigned char byte, hipStream_t st)
 {
     if (bytes == 0) return;
+    const unsigned word = 0x01010101u * byte;
     const size_t n16 = bytes / 16;
     const int ntail = (int)(bytes % 16);
     size_t blocks = (n16 + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     if (blocks == 0) blocks = 1;
-    zero_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>((uint4*)p, n16, (unsigned char*)p + n16 * 16, ntail);
+    fill_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>((uint4*)p, n16, (unsigned char*)p + n16 * 16, ntail, word);
 }
 
 }  // namespace fpdt

@@ -139,5 +139,6 @@ void launch_merge(const void* Oa, const float* La, const void* Ob, const float* 
 
 // zero-fill by kernel (safe under graph capture)
 void launch_zero(void* p, size_t bytes, hipStream_t st);
+void launch_fill_bytes(void* p, size_t bytes, unsigned char byte, hipStream_t st);
 
 }  // namespace fpdt

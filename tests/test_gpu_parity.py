@@ -96,6 +96,31 @@ def test_offload_is_bitwise_equal_to_pairwise(flags):
     print(parity.check_all(out, ref, True))
 
 
+@pytest.mark.parametrize("flags", [B.FPDT_KV_ON_HOST | B.FPDT_BWD_KV_OUTER,
+                                   B.FPDT_KV_ON_HOST | B.FPDT_BWD_Q_OUTER,
+                                   B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST])
+def test_offload_event_ordering_with_poisoned_buffers_and_delayed_copies(flags):
+    """Every staging buffer is filled with NaNs right before the copy into it and every copy is
+    held back by a 48 MiB dummy copy on its stream: a kernel that does not wait for its data, or
+    a copy / kernel that does not wait for a buffer to be released, changes the result."""
+    S, chunk, Hq, Hkv, D = 4096, 512, 8, 2, 128
+    announce("offload under poison + delay", S, chunk, flags)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=6)
+    scale = D ** -0.5
+    order = B.FPDT_BWD_Q_OUTER if (flags & (B.FPDT_BWD_Q_OUTER | B.FPDT_ACT_ON_HOST)) else B.FPDT_BWD_KV_OUTER
+    base = run(Q, K, V, dO, chunk, scale, B.FPDT_PAIRWISE | order)
+    B.fpdt_debug_configure(B.FPDT_DEBUG_POISON_STAGING | B.FPDT_DEBUG_DELAY_COPIES)
+    try:
+        out = run(Q, K, V, dO, chunk, scale, flags)
+    finally:
+        B.fpdt_debug_configure(0)
+    for n in ("O", "LSE", "dQ", "dK", "dV"):
+        assert torch.isfinite(out[n].float()).all(), n
+        assert torch.equal(out[n].cpu(), base[n].cpu()), n
+    with pytest.raises(B.FpdtError):
+        B.fpdt_debug_configure(1 << 7)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_merge_kernel(dtype):
     rows, Hq, D = 1000, 4, 80
