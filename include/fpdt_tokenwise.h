@@ -1,0 +1,65 @@
+/*
+ * fpdt_tokenwise.h -- C ABI of the token-wise chunked neighbours of the attention path
+ * (Sec. 5.4, "Chunk Granularity"): operations whose cost is linear in the sequence length and
+ * whose intermediate buffers, not their FLOPs, are the problem at long sequences.  They are
+ * chunked along the sequence without offloading; the intermediates exist for one chunk at a
+ * time.
+ *
+ *   fpdt_tw_loss_fwd_bwd   softmax cross-entropy over the vocabulary with its last linear
+ *                          projection, forward and backward fused per chunk: the fp32 logits
+ *                          [rows, vocab] never exist for more than one chunk (the paper's
+ *                          "memory spike ... in the final calculation of softmax and
+ *                          cross-entropy loss"; suggested chunk count: vocab / hidden * 2).
+ *
+ * The dense products are plain library GEMMs (rocBLAS, bf16 inputs, fp32 accumulation); the
+ * row-wise softmax / loss / gradient is a HIP kernel of this library.  Built as a separate
+ * shared library (libfpdt_tokenwise.so) so that the attention library has no BLAS dependency.
+ *
+ * Conventions as in fpdt.h: row-major contiguous tensors, device pointers, caller-owned
+ * buffers, `stream` is a hipStream_t passed as void*, calls only enqueue, every function returns
+ * an fpdt status code (0 = OK, 1 = invalid argument, 2 = unsupported, 3 = workspace, 4 = HIP or
+ * rocBLAS failure; text from fpdt_tw_last_error).  The library creates one rocBLAS handle per
+ * process on first use (rocBLAS may allocate its own device workspace).
+ */
+#ifndef FPDT_TOKENWISE_H
+#define FPDT_TOKENWISE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Bytes of device workspace fpdt_tw_loss_fwd_bwd needs: one chunk of fp32 logits and one chunk
+ * of bf16 logit gradients, chunk = ceil(rows / n_chunks) rows.  0 if the arguments are invalid. */
+size_t fpdt_tw_loss_workspace_bytes(int64_t rows, int hidden, int vocab, int n_chunks);
+
+/*
+ * Chunked cross-entropy loss with its output projection (Sec. 5.4).  For every row r:
+ *     logits_r = H_r W^T                      (bf16 x bf16 -> fp32)
+ *     lse_r    = log sum_v exp(logits_r[v])   (fp32, max-subtracted)
+ *     loss_r   = lse_r - logits_r[target_r]
+ * and, when dH / dW are given, the gradient of sum_r grad_scale * loss_r:
+ *     G_r  = grad_scale * (softmax(logits_r) - onehot(target_r))    (rounded to bf16)
+ *     dH_r = G_r W                            (written, bf16)
+ *     dW  += G^T H                            (ACCUMULATED into the caller's fp32 buffer)
+ *   H [rows, hidden] bf16, W [vocab, hidden] bf16, target [rows] int32 in [0, vocab)   in
+ *   loss, lse [rows] fp32                                                             out
+ *   dH [rows, hidden] bf16 or NULL, dW [vocab, hidden] fp32 or NULL                   out / in-out
+ *   workspace: device memory, 256-byte aligned, >= fpdt_tw_loss_workspace_bytes(...)
+ * A target outside [0, vocab) is not detected (its row's loss is lse_r and its gradient the
+ * plain softmax).
+ */
+int fpdt_tw_loss_fwd_bwd(const void *H, const void *W, const int32_t *target, float grad_scale,
+                         float *loss, float *lse, void *dH, float *dW, int64_t rows, int hidden,
+                         int vocab, int n_chunks, void *workspace, size_t workspace_bytes,
+                         void *stream);
+
+/* Text describing the calling thread's most recent error ("" if none). Never NULL. */
+const char *fpdt_tw_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FPDT_TOKENWISE_H */

@@ -1,4 +1,4 @@
-"""Build libfpdt.so (HIP kernels + C ABI) for gfx950, in-tree.
+"""Build libfpdt.so (HIP kernels + C ABI) and libfpdt_tokenwise.so for gfx950, in-tree.
 
     python -m paper_2408_16978_amd.build
 
@@ -15,6 +15,9 @@ SRC_DIR = os.path.join(PKG, "csrc")
 BUILD_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libfpdt.so")
 SOURCES = ["api.hip", "pack.hip", "fwd_bf16.hip", "bwd_bf16.hip", "f32_path.hip"]
+# token-wise chunked neighbours (library GEMMs): a library of their own, linked against rocBLAS
+TW_LIB = os.path.join(PKG, "libfpdt_tokenwise.so")
+TW_SOURCES = ["tokenwise.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops off: packed fp32 VALU forms are kept out of the generated code.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -34,14 +37,17 @@ def _compile(name: str) -> str:
 
 def build(verbose: bool = False) -> str:
     os.makedirs(BUILD_DIR, exist_ok=True)
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n%s" % r.stderr)
-    if verbose:
-        print("built", LIB)
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + len(TW_SOURCES))) as ex:
+        objs = list(ex.map(_compile, SOURCES + TW_SOURCES))
+    tw_objs = objs[len(SOURCES):]
+    objs = objs[:len(SOURCES)]
+    for lib, o, extra in ((LIB, objs, []), (TW_LIB, tw_objs, ["-lrocblas"])):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + o + extra
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n%s" % r.stderr)
+        if verbose:
+            print("built", lib)
     return LIB
 
 
