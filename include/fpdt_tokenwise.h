@@ -10,6 +10,9 @@
  *                          [rows, vocab] never exist for more than one chunk (the paper's
  *                          "memory spike ... in the final calculation of softmax and
  *                          cross-entropy loss"; suggested chunk count: vocab / hidden * 2).
+ *   fpdt_tw_linear_*       the per-chunk QKV projection in front of the attention.
+ *   fpdt_tw_ffn_*          the feed-forward block, chunked with twice the attention's chunk
+ *                          count, forward and (recomputing) backward.
  *
  * The dense products are plain library GEMMs (rocBLAS, bf16 inputs, fp32 accumulation); the
  * row-wise softmax / loss / gradient is a HIP kernel of this library.  Built as a separate
@@ -55,6 +58,40 @@ int fpdt_tw_loss_fwd_bwd(const void *H, const void *W, const int32_t *target, fl
                          float *loss, float *lse, void *dH, float *dW, int64_t rows, int hidden,
                          int vocab, int n_chunks, void *workspace, size_t workspace_bytes,
                          void *stream);
+
+/*
+ * Chunked linear projection (Sec. 4.1: every sequence chunk T_i is projected to q_i, k_i, v_i on
+ * its own, so that chunk i's attention can start while chunk i+1 is still being projected).
+ *     Y = X W^T          X [rows, n_in] bf16, W [n_out, n_in] bf16  ->  Y [rows, n_out] bf16
+ * computed ceil(rows / n_chunks) rows at a time; needs no workspace.  Backward:
+ *     dX = dY W  (written, bf16; NULL to skip),   dW += dY^T X  (accumulated, fp32; NULL to skip)
+ */
+int fpdt_tw_linear_fwd(const void *X, const void *W, void *Y, int64_t rows, int n_in, int n_out,
+                       int n_chunks, void *stream);
+int fpdt_tw_linear_bwd(const void *X, const void *W, const void *dY, void *dX, float *dW,
+                       int64_t rows, int n_in, int n_out, int n_chunks, void *stream);
+
+/*
+ * Chunked feed-forward block (Sec. 5.4: token-wise, its [rows, n_ffn] intermediates are what has
+ * to be bounded; twice the attention's chunk count is enough, and nothing is offloaded).
+ *   FPDT_TW_GELU    Y = gelu(X W1^T) W2^T                      (GPT; exact erf form)
+ *   FPDT_TW_SWIGLU  Y = (silu(X W1^T) * (X W3^T)) W2^T         (Llama)
+ *   X, Y, dX, dY [rows, n_model] bf16; W1, W3 [n_ffn, n_model] bf16; W2 [n_model, n_ffn] bf16
+ *   (W3, dW3: SWIGLU only, NULL otherwise).  Intermediates are rounded to bf16 between GEMMs.
+ * The backward recomputes the pre-activations of a chunk from X (the forward saves nothing),
+ * writes dX and ACCUMULATES into the caller's fp32 dW1, dW3, dW2 (each may be NULL to skip).
+ *   workspace: device memory, 256-byte aligned, >= fpdt_tw_ffn_workspace_bytes(..., is_bwd)
+ */
+enum { FPDT_TW_GELU = 0, FPDT_TW_SWIGLU = 1 };
+size_t fpdt_tw_ffn_workspace_bytes(int64_t rows, int n_model, int n_ffn, int act, int n_chunks,
+                                   int is_bwd);
+int fpdt_tw_ffn_fwd(const void *X, const void *W1, const void *W3, const void *W2, void *Y,
+                    int64_t rows, int n_model, int n_ffn, int act, int n_chunks, void *workspace,
+                    size_t workspace_bytes, void *stream);
+int fpdt_tw_ffn_bwd(const void *X, const void *W1, const void *W3, const void *W2, const void *dY,
+                    void *dX, float *dW1, float *dW3, float *dW2, int64_t rows, int n_model,
+                    int n_ffn, int act, int n_chunks, void *workspace, size_t workspace_bytes,
+                    void *stream);
 
 /* Text describing the calling thread's most recent error ("" if none). Never NULL. */
 const char *fpdt_tw_last_error(void);

@@ -10,6 +10,10 @@ LIB_PATH = os.path.join(_PKG, "libfpdt_tokenwise.so")
 _lib = None
 
 
+FPDT_TW_GELU = 0
+FPDT_TW_SWIGLU = 1
+
+
 class FpdtTwError(RuntimeError):
     def __init__(self, status, text):
         super().__init__("fpdt_tw status %d: %s" % (status, text))
@@ -28,6 +32,16 @@ def load():
     L.fpdt_tw_loss_workspace_bytes.argtypes = [i64, ci, ci, ci]
     L.fpdt_tw_loss_fwd_bwd.restype = ci
     L.fpdt_tw_loss_fwd_bwd.argtypes = [vp, vp, vp, cf, vp, vp, vp, vp, i64, ci, ci, ci, vp, sz, vp]
+    L.fpdt_tw_linear_fwd.restype = ci
+    L.fpdt_tw_linear_fwd.argtypes = [vp, vp, vp, i64, ci, ci, ci, vp]
+    L.fpdt_tw_linear_bwd.restype = ci
+    L.fpdt_tw_linear_bwd.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, ci, vp]
+    L.fpdt_tw_ffn_workspace_bytes.restype = sz
+    L.fpdt_tw_ffn_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci]
+    L.fpdt_tw_ffn_fwd.restype = ci
+    L.fpdt_tw_ffn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, sz, vp]
+    L.fpdt_tw_ffn_bwd.restype = ci
+    L.fpdt_tw_ffn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, sz, vp]
     L.fpdt_tw_last_error.restype = ctypes.c_char_p
     _lib = L
     return L
@@ -58,3 +72,48 @@ def fpdt_tw_loss_fwd_bwd(H, W, target, grad_scale, loss, lse, dH, dW, n_chunks, 
                                      stream.cuda_stream)
     if st != 0:
         raise FpdtTwError(st, fpdt_tw_last_error())
+
+
+def _check(st):
+    if st != 0:
+        raise FpdtTwError(st, fpdt_tw_last_error())
+
+
+def _stream(stream):
+    return (torch.cuda.current_stream() if stream is None else stream).cuda_stream
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def fpdt_tw_linear_fwd(X, W, Y, n_chunks, stream=None):
+    """Y [rows, n_out] = X [rows, n_in] W^T, W [n_out, n_in]; all bf16."""
+    rows, n_in = X.shape
+    _check(load().fpdt_tw_linear_fwd(_ptr(X), _ptr(W), _ptr(Y), rows, n_in, W.shape[0], n_chunks, _stream(stream)))
+
+
+def fpdt_tw_linear_bwd(X, W, dY, dX, dW, n_chunks, stream=None):
+    """dX (bf16, written, or None) = dY W;  dW (fp32, accumulated into, or None) += dY^T X."""
+    rows, n_in = X.shape
+    _check(load().fpdt_tw_linear_bwd(_ptr(X), _ptr(W), _ptr(dY), _ptr(dX), _ptr(dW), rows, n_in, W.shape[0],
+                                     n_chunks, _stream(stream)))
+
+
+def fpdt_tw_ffn_workspace_bytes(rows, n_model, n_ffn, act, n_chunks, is_bwd) -> int:
+    return int(load().fpdt_tw_ffn_workspace_bytes(rows, n_model, n_ffn, act, n_chunks, int(bool(is_bwd))))
+
+
+def fpdt_tw_ffn_fwd(X, W1, W3, W2, Y, act, n_chunks, workspace, stream=None):
+    """X, Y [rows, n_model] bf16; W1, W3 [n_ffn, n_model]; W2 [n_model, n_ffn]; W3 None for GELU."""
+    rows, n_model = X.shape
+    _check(load().fpdt_tw_ffn_fwd(_ptr(X), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(Y), rows, n_model, W1.shape[0], act,
+                                  n_chunks, _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def fpdt_tw_ffn_bwd(X, W1, W3, W2, dY, dX, dW1, dW3, dW2, act, n_chunks, workspace, stream=None):
+    """dX bf16 (written); dW1, dW3, dW2 fp32 (accumulated into; any may be None)."""
+    rows, n_model = X.shape
+    _check(load().fpdt_tw_ffn_bwd(_ptr(X), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(dY), _ptr(dX), _ptr(dW1), _ptr(dW3),
+                                  _ptr(dW2), rows, n_model, W1.shape[0], act, n_chunks, _ptr(workspace),
+                                  _nbytes(workspace), _stream(stream)))

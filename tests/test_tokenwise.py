@@ -55,6 +55,65 @@ def test_cross_entropy_oracle_closed_forms():
     np.testing.assert_allclose(out2["loss"], out["loss"], atol=1e-12)
 
 
+@pytest.mark.parametrize("swiglu", [False, True])
+def test_ffn_and_linear_oracles_against_torch_autograd(swiglu):
+    r = np.random.default_rng(3 + swiglu)
+    rows, n_model, n_ffn = 23, 12, 29
+    X, dY = r.standard_normal((rows, n_model)), r.standard_normal((rows, n_model))
+    W1, W3 = r.standard_normal((n_ffn, n_model)), r.standard_normal((n_ffn, n_model))
+    W2 = r.standard_normal((n_model, n_ffn))
+    out = otw.ffn(X, W1, W2, W3 if swiglu else None, dY)
+    x, w1, w3, w2 = (torch.tensor(a, requires_grad=True) for a in (X, W1, W3, W2))
+    F = torch.nn.functional
+    y = (F.silu(x @ w1.T) * (x @ w3.T)) @ w2.T if swiglu else F.gelu(x @ w1.T) @ w2.T
+    (y * torch.tensor(dY)).sum().backward()
+    np.testing.assert_allclose(out["Y"], y.detach().numpy(), rtol=1e-11, atol=1e-12)
+    for k, t in (("dX", x), ("dW1", w1), ("dW2", w2)) + ((("dW3", w3),) if swiglu else ()):
+        np.testing.assert_allclose(out[k], t.grad.numpy(), rtol=1e-10, atol=1e-11, err_msg=k)
+    assert ("dW3" in out) == swiglu
+    # the linear projection is the FFN's first GEMM: pin it the same way
+    x2, w = torch.tensor(X, requires_grad=True), torch.tensor(W1, requires_grad=True)
+    dy2 = r.standard_normal((rows, n_ffn))
+    lin = otw.linear(X, W1, dY=dy2)
+    ((x2 @ w.T) * torch.tensor(dy2)).sum().backward()
+    np.testing.assert_allclose(lin["Y"], (x2 @ w.T).detach().numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lin["dX"], x2.grad.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lin["dW"], w.grad.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_ffn_oracle_closed_forms_and_finite_differences():
+    r = np.random.default_rng(5)
+    rows, n_model, n_ffn = 5, 4, 6
+    X = r.standard_normal((rows, n_model))
+    W1, W3 = r.standard_normal((n_ffn, n_model)), r.standard_normal((n_ffn, n_model))
+    W2 = r.standard_normal((n_model, n_ffn))
+    # gelu(0) = silu(0) = 0: X = 0 gives Y = 0; gelu'(0) = silu'(0) = 1/2
+    z = np.zeros_like(X)
+    assert np.all(otw.ffn(z, W1, W2)["Y"] == 0) and np.all(otw.ffn(z, W1, W2, W3)["Y"] == 0)
+    dY = r.standard_normal((rows, n_model))
+    np.testing.assert_allclose(otw.ffn(z, W1, W2, None, dY)["dX"], 0.5 * dY @ W2 @ W1, atol=1e-14)
+    # large positive pre-activations: gelu(a) -> a, so the block is the product of its two matrices
+    Xp, W1p = np.abs(X) + 1, np.abs(W1) * 10 + 10
+    np.testing.assert_allclose(otw.ffn(Xp, W1p, W2)["Y"], Xp @ W1p.T @ W2.T, rtol=1e-12)
+    # large negative: gelu(a) -> 0
+    np.testing.assert_allclose(otw.ffn(Xp, -W1p, W2)["Y"], 0, atol=1e-12)
+    # SwiGLU is linear in W3 and in W2
+    a = otw.ffn(X, W1, W2, W3)["Y"]
+    np.testing.assert_allclose(otw.ffn(X, W1, W2, 3 * W3)["Y"], 3 * a, rtol=1e-13)
+    # central finite differences of L = sum(Y * dY) in one coordinate of each argument
+    eps = 1e-6
+    for sw in (False, True):
+        g = otw.ffn(X, W1, W2, W3 if sw else None, dY)
+        L = lambda X_, W1_, W2_, W3_: float((otw.ffn(X_, W1_, W2_, W3_ if sw else None)["Y"] * dY).sum())
+        for name, arr, idx in (("dX", 0, (2, 1)), ("dW1", 1, (3, 2)), ("dW2", 2, (1, 4))) + ((("dW3", 3, (5, 0)),) if sw else ()):
+            args_p = [X.copy(), W1.copy(), W2.copy(), W3.copy()]
+            args_m = [X.copy(), W1.copy(), W2.copy(), W3.copy()]
+            args_p[arr][idx] += eps
+            args_m[arr][idx] -= eps
+            fd = (L(*args_p) - L(*args_m)) / (2 * eps)
+            assert abs(fd - g[name][idx]) < 1e-6 * max(1.0, abs(fd)), (sw, name, fd, g[name][idx])
+
+
 # ------------------------------------------------------------------ host-side ABI checks (CPU)
 def test_tokenwise_library_exports_and_rejects_bad_arguments():
     text = open(os.path.join(ROOT, "include", "fpdt_tokenwise.h")).read()
@@ -81,6 +140,20 @@ def test_tokenwise_library_exports_and_rejects_bad_arguments():
     assert call(ws=None) == 3
     assert call(wsb=16) == 3
     assert call(ws=0x100010) == 3
+    # feed-forward workspace: [chunk, n_ffn] bf16 tiles, 2 (GELU) or 3 (SwiGLU), one more backward
+    tile = (250 * 1024 * 2 + 255) // 256 * 256
+    assert TW.fpdt_tw_ffn_workspace_bytes(1000, 256, 1024, TW.FPDT_TW_GELU, 4, False) == 2 * tile
+    assert TW.fpdt_tw_ffn_workspace_bytes(1000, 256, 1024, TW.FPDT_TW_SWIGLU, 4, False) == 3 * tile
+    assert TW.fpdt_tw_ffn_workspace_bytes(1000, 256, 1024, TW.FPDT_TW_SWIGLU, 4, True) == 4 * tile
+    assert TW.fpdt_tw_ffn_workspace_bytes(1000, 256, 1024, 7, 4, True) == 0
+    assert L.fpdt_tw_ffn_fwd(p, p, None, p, p, 1000, 256, 1024, TW.FPDT_TW_SWIGLU, 4, 0x100000, 1 << 40, None) == 1
+    assert "W3" in TW.fpdt_tw_last_error()
+    assert L.fpdt_tw_ffn_fwd(p, p, None, p, p, 1000, 256, 1024, TW.FPDT_TW_GELU, 4, 0x100000, 16, None) == 3
+    assert L.fpdt_tw_ffn_bwd(p, p, None, p, p, None, None, None, None, 1000, 256, 1024, TW.FPDT_TW_GELU, 4,
+                             0x100000, 1 << 40, None) == 1
+    assert L.fpdt_tw_linear_fwd(p, p, None, 1000, 256, 768, 4, None) == 1
+    assert L.fpdt_tw_linear_fwd(p, p, p, 1000, 256, 768, 0, None) == 1
+    assert L.fpdt_tw_linear_bwd(p, p, p, None, None, 1000, 0, 768, 4, None) == 1
 
 
 # ------------------------------------------------------------------ GPU parity
@@ -137,3 +210,86 @@ def test_gpu_loss_rejects_small_workspace():
     with pytest.raises(TW.FpdtTwError) as e:
         TW.fpdt_tw_loss_fwd_bwd(H.cuda(), W.cuda(), t.cuda(), 1.0, out, out.clone(), None, None, 1, ws)
     assert e.value.status == 3
+
+
+def _rowwise_ok(name, got, ref, rel=2e-2):
+    """|got - ref| <= rel * rms(ref row) + half a bf16 ulp of ref (at most 2^-8 |ref|: 8 significand
+    bits), element by element."""
+    rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))
+    budget = rel * rms + 2.0 ** -8 * np.abs(ref) + 1e-9
+    err = np.abs(got - ref)
+    assert (err <= budget).all(), (name, float((err / budget).max()))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("rows,n_in,n_out,n_chunks", [(1000, 256, 768, 3), (333, 136, 520, 7)])
+def test_gpu_linear_matches_oracle(rows, n_in, n_out, n_chunks):
+    print("[case] chunked linear", rows, n_in, n_out, n_chunks, flush=True)
+    g = torch.Generator().manual_seed(41)
+    X = torch.randn(rows, n_in, generator=g).to(torch.bfloat16)
+    W = (torch.randn(n_out, n_in, generator=g) * n_in ** -0.5).to(torch.bfloat16)
+    dY = torch.randn(rows, n_out, generator=g).to(torch.bfloat16)
+    ref = otw.linear(X.double().numpy(), W.double().numpy(), dY.double().numpy())
+    Xd, Wd, dYd = X.cuda(), W.cuda(), dY.cuda()
+    Y = torch.empty(rows, n_out, dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty_like(Xd)
+    dW = torch.zeros(n_out, n_in, device="cuda")
+    TW.fpdt_tw_linear_fwd(Xd, Wd, Y, n_chunks)
+    TW.fpdt_tw_linear_bwd(Xd, Wd, dYd, dX, dW, n_chunks)
+    torch.cuda.synchronize()
+    # fp32 accumulation of exact products, one rounding to bf16 on store
+    _rowwise_ok("Y", Y.float().cpu().numpy(), ref["Y"], rel=1e-4)
+    _rowwise_ok("dX", dX.float().cpu().numpy(), ref["dX"], rel=1e-4)
+    np.testing.assert_allclose(dW.cpu().numpy(), ref["dW"], atol=1e-4 * float(np.abs(ref["dW"]).max()))
+    # one chunk gives the same bits for Y and dX (each row is its own dot products)
+    Y1, dX1 = torch.empty_like(Y), torch.empty_like(dX)
+    TW.fpdt_tw_linear_fwd(Xd, Wd, Y1, 1)
+    TW.fpdt_tw_linear_bwd(Xd, Wd, dYd, dX1, None, 1)
+    torch.cuda.synchronize()
+    _rowwise_ok("Y vs one chunk", Y.float().cpu().numpy(), Y1.float().cpu().numpy().astype(np.float64), rel=1e-4)
+    _rowwise_ok("dX vs one chunk", dX.float().cpu().numpy(), dX1.float().cpu().numpy().astype(np.float64), rel=1e-4)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("act,rows,n_model,n_ffn,n_chunks", [
+    ("gelu", 1000, 256, 1024, 4), ("swiglu", 1000, 256, 688, 4), ("swiglu", 257, 128, 349, 5), ("gelu", 64, 64, 256, 1)])
+def test_gpu_ffn_matches_oracle(act, rows, n_model, n_ffn, n_chunks):
+    print("[case] chunked ffn", act, rows, n_model, n_ffn, n_chunks, flush=True)
+    sw = act == "swiglu"
+    code = TW.FPDT_TW_SWIGLU if sw else TW.FPDT_TW_GELU
+    g = torch.Generator().manual_seed(43)
+    X = torch.randn(rows, n_model, generator=g).to(torch.bfloat16)
+    W1 = (torch.randn(n_ffn, n_model, generator=g) * n_model ** -0.5).to(torch.bfloat16)
+    W3 = (torch.randn(n_ffn, n_model, generator=g) * n_model ** -0.5).to(torch.bfloat16)
+    W2 = (torch.randn(n_model, n_ffn, generator=g) * n_ffn ** -0.5).to(torch.bfloat16)
+    dY = torch.randn(rows, n_model, generator=g).to(torch.bfloat16)
+    f64 = lambda t: t.double().numpy()
+    ref = otw.ffn(f64(X), f64(W1), f64(W2), f64(W3) if sw else None, f64(dY))
+    Xd, W1d, W2d, dYd = X.cuda(), W1.cuda(), W2.cuda(), dY.cuda()
+    W3d = W3.cuda() if sw else None
+    Y, dX = torch.empty_like(Xd), torch.empty_like(Xd)
+    dW1 = torch.zeros(n_ffn, n_model, device="cuda")
+    dW3 = torch.zeros(n_ffn, n_model, device="cuda") if sw else None
+    dW2 = torch.zeros(n_model, n_ffn, device="cuda")
+    wf = torch.empty(TW.fpdt_tw_ffn_workspace_bytes(rows, n_model, n_ffn, code, n_chunks, False), dtype=torch.uint8, device="cuda")
+    wb = torch.empty(TW.fpdt_tw_ffn_workspace_bytes(rows, n_model, n_ffn, code, n_chunks, True), dtype=torch.uint8, device="cuda")
+    TW.fpdt_tw_ffn_fwd(Xd, W1d, W3d, W2d, Y, code, n_chunks, wf)
+    TW.fpdt_tw_ffn_bwd(Xd, W1d, W3d, W2d, dYd, dX, dW1, dW3, dW2, code, n_chunks, wb)
+    torch.cuda.synchronize()
+    # intermediates [chunk, n_ffn] are rounded to bf16 between GEMMs (relative 2^-9 each, independent
+    # across the contraction): 2e-2 of the reference row's RMS covers them with a wide margin
+    _rowwise_ok("Y", Y.float().cpu().numpy(), ref["Y"])
+    _rowwise_ok("dX", dX.float().cpu().numpy(), ref["dX"])
+    _rowwise_ok("dW1", dW1.cpu().numpy(), ref["dW1"])
+    _rowwise_ok("dW2", dW2.cpu().numpy(), ref["dW2"])
+    if sw:
+        _rowwise_ok("dW3", dW3.cpu().numpy(), ref["dW3"])
+    # the weight gradients are accumulated into, dX is overwritten
+    TW.fpdt_tw_ffn_bwd(Xd, W1d, W3d, W2d, dYd, dX, dW1, None, None, code, n_chunks, wb)
+    torch.cuda.synchronize()
+    _rowwise_ok("dW1 twice", dW1.cpu().numpy(), 2 * ref["dW1"])
+    _rowwise_ok("dX again", dX.float().cpu().numpy(), ref["dX"])
+    _rowwise_ok("dW2 untouched", dW2.cpu().numpy(), ref["dW2"])
+    if n_chunks > 1:
+        w1 = TW.fpdt_tw_ffn_workspace_bytes(rows, n_model, n_ffn, code, 1, True)
+        assert wb.numel() * 2 < w1
