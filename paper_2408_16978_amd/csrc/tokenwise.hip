@@ -114,15 +114,28 @@ __global__ __launch_bounds__(256) void loss_rows_kernel(const float* __restrict_
     __shared__ float red[2][4];
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const float* x = logits + (size_t)row * vocab;
-    // running (max, sum of exp) per thread, merged across the workgroup
+    // running (max, sum of exp) per thread, merged across the workgroup; rows are 16-byte
+    // aligned when vocab % 4 == 0 (the base is), and then read four logits per access
+    const bool vec = (vocab & 3) == 0;
     float m = -INFINITY, l = 0.f;
-    for (int v = tid; v < vocab; v += 256) {
-        const float a = x[v];
-        if (a > m) {
-            l = l * __expf(m - a) + 1.f;
-            m = a;
-        } else {
-            l += __expf(a - m);
+    if (vec) {
+        const float4* x4 = reinterpret_cast<const float4*>(x);
+        for (int v = tid; v < vocab / 4; v += 256) {
+            const float4 a = x4[v];
+            const float mn = fmaxf(fmaxf(fmaxf(a.x, a.y), fmaxf(a.z, a.w)), m);
+            if (mn == -INFINITY) continue;  // nothing finite yet: exp(-inf - -inf) is not a number
+            l = l * __expf(m - mn) + __expf(a.x - mn) + __expf(a.y - mn) + __expf(a.z - mn) + __expf(a.w - mn);
+            m = mn;
+        }
+    } else {
+        for (int v = tid; v < vocab; v += 256) {
+            const float a = x[v];
+            if (a > m) {
+                l = l * __expf(m - a) + 1.f;
+                m = a;
+            } else {
+                l += __expf(a - m);
+            }
         }
     }
     const float wm = wave_max(m);
@@ -141,6 +154,20 @@ __global__ __launch_bounds__(256) void loss_rows_kernel(const float* __restrict_
     }
     if (!G) return;
     uint16_t* g = G + (size_t)row * vocab;
+    if (vec) {
+        const float4* x4 = reinterpret_cast<const float4*>(x);
+        uint2* g2 = reinterpret_cast<uint2*>(g);
+        for (int v = tid; v < vocab / 4; v += 256) {
+            const float4 a = x4[v];
+            const int d = t - 4 * v;  // 0..3 when the target is one of these four
+            const unsigned p0 = to_bf16(grad_scale * (__expf(a.x - lse) - (d == 0 ? 1.f : 0.f)));
+            const unsigned p1 = to_bf16(grad_scale * (__expf(a.y - lse) - (d == 1 ? 1.f : 0.f)));
+            const unsigned p2 = to_bf16(grad_scale * (__expf(a.z - lse) - (d == 2 ? 1.f : 0.f)));
+            const unsigned p3 = to_bf16(grad_scale * (__expf(a.w - lse) - (d == 3 ? 1.f : 0.f)));
+            g2[v] = make_uint2(p0 | (p1 << 16), p2 | (p3 << 16));
+        }
+        return;
+    }
     for (int v = tid; v < vocab; v += 256) {
         const float p = __expf(x[v] - lse) - (v == t ? 1.f : 0.f);
         g[v] = to_bf16(grad_scale * p);
