@@ -4,6 +4,7 @@
 // chunk pair runs when, where its operands live, and which copies overlap which kernels.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -241,10 +242,12 @@ int get_ctx(DeviceCtx** out)
     if (dev < 0 || dev >= 64) return fail(FPDT_ERR_HIP, "device index %d out of range", dev);
     DeviceCtx& c = g_ctx[dev];
     if (!c.ready) {
-        // default priority on purpose: work on streams of unequal priority is avoided
-        HIP_TRY(hipStreamCreateWithFlags(&c.h2d, hipStreamNonBlocking));
-        HIP_TRY(hipStreamCreateWithFlags(&c.d2h, hipStreamNonBlocking));
-        for (int i = 0; i < EV_COUNT; ++i) HIP_TRY(hipEventCreateWithFlags(&c.ev[i], hipEventDisableTiming));
+        // default priority on purpose: work on streams of unequal priority is avoided; a call
+        // that fails half way keeps what it made, and the next call makes only the rest
+        if (!c.h2d) HIP_TRY(hipStreamCreateWithFlags(&c.h2d, hipStreamNonBlocking));
+        if (!c.d2h) HIP_TRY(hipStreamCreateWithFlags(&c.d2h, hipStreamNonBlocking));
+        for (int i = 0; i < EV_COUNT; ++i)
+            if (!c.ev[i]) HIP_TRY(hipEventCreateWithFlags(&c.ev[i], hipEventDisableTiming));
         c.ready = true;
     }
     *out = &c;
@@ -298,7 +301,7 @@ int launch_status(const char* what)
 
 // ---- optional per-kernel timing (benchmarks): HIP events around every launch ----
 struct ProfRec { int kind; hipEvent_t a, b; };
-bool g_prof_on = false;
+std::atomic<bool> g_prof_on{false};
 std::vector<ProfRec> g_prof;
 std::mutex g_prof_mu;
 
@@ -308,10 +311,18 @@ struct ProfScope {
     bool live = false;
     ProfScope(int kind, hipStream_t s) : st(s)
     {
-        if (!g_prof_on) return;
-        if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+        if (!g_prof_on.load(std::memory_order_relaxed)) return;
+        if (hipEventCreate(&r.a) != hipSuccess) return;
+        if (hipEventCreate(&r.b) != hipSuccess) {
+            (void)hipEventDestroy(r.a);
+            return;
+        }
         r.kind = kind;
         live = hipEventRecord(r.a, st) == hipSuccess;
+        if (!live) {
+            (void)hipEventDestroy(r.a);
+            (void)hipEventDestroy(r.b);
+        }
     }
     ~ProfScope()
     {
@@ -949,9 +960,17 @@ int fpdt_debug_configure(unsigned flags)
         DeviceCtx* c = nullptr;
         TRY(get_ctx(&c));
         if (!c->delay_host) {
-            HIP_TRY(hipHostMalloc(&c->delay_host, DELAY_BYTES, hipHostMallocDefault));
-            HIP_TRY(hipMalloc(&c->delay_dev, DELAY_BYTES));
-            memset(c->delay_host, 0, DELAY_BYTES);
+            void* h = nullptr;
+            HIP_TRY(hipHostMalloc(&h, DELAY_BYTES, hipHostMallocDefault));
+            memset(h, 0, DELAY_BYTES);
+            if (!c->delay_dev) {
+                hipError_t e = hipMalloc(&c->delay_dev, DELAY_BYTES);
+                if (e != hipSuccess) {
+                    (void)hipHostFree(h);
+                    return fail(FPDT_ERR_HIP, "hipMalloc of the delay buffer failed: %s", hipGetErrorString(e));
+                }
+            }
+            c->delay_host = h;
         }
     }
     g_debug = flags;
