@@ -7,7 +7,8 @@ from oracle import definition
 F32_TOL = 1e-4        # max-abs, fp32 tensors
 # bf16 tensors, per (row, head) and element d:
 #   |x - ref| <= BF16_TOL * rms_d(ref[row, head, :])   compute error, relative to the row's RMS
-#              + BF16_HALF_ULP * |ref|                  storing the result as bf16 (round to nearest)
+#              + BF16_HALF_ULP * |ref|                  storing the result as bf16 (half an ulp is between
+#                                                       2^-9 |x| and 2^-8 |x|; the smaller figure is granted)
 #              + BF16_FLOOR                             fp32 round-off where the exact value is ~0
 BF16_TOL = 2e-2
 BF16_HALF_ULP = 2.0 ** -9
