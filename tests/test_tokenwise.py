@@ -293,3 +293,66 @@ def test_gpu_ffn_matches_oracle(act, rows, n_model, n_ffn, n_chunks):
     if n_chunks > 1:
         w1 = TW.fpdt_tw_ffn_workspace_bytes(rows, n_model, n_ffn, code, 1, True)
         assert wb.numel() * 2 < w1
+
+
+# ------------------------------------------------------------------ Llama-8B widths, sampled
+@pytest.mark.gpu
+def test_gpu_ffn_llama_widths_sampled_rows_and_weight_slices():
+    """Model 4096, FFN 14336, SwiGLU, 8192 tokens in 4 chunks.  Rows are independent, so the
+    oracle evaluated on sampled rows gives their Y and dX exactly; a hidden unit's weight
+    gradients depend only on its own column of the intermediates, so the oracle evaluated on
+    a slice of hidden units gives those rows of dW1 / dW3 and columns of dW2 exactly."""
+    rows, n_model, n_ffn, n_chunks = 8192, 4096, 14336, 4
+    print("[case] ffn llama widths", rows, n_model, n_ffn, n_chunks, flush=True)
+    g = torch.Generator(device="cuda").manual_seed(47)
+    bf = lambda *s, std=1.0: (torch.randn(*s, device="cuda", generator=g) * std).to(torch.bfloat16)
+    X, dY = bf(rows, n_model), bf(rows, n_model)
+    W1, W3, W2 = bf(n_ffn, n_model, std=n_model ** -0.5), bf(n_ffn, n_model, std=n_model ** -0.5), bf(n_model, n_ffn, std=n_ffn ** -0.5)
+    code = TW.FPDT_TW_SWIGLU
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+    dW1, dW3, dW2 = (torch.zeros_like(w, dtype=torch.float32) for w in (W1, W3, W2))
+    wb = torch.empty(TW.fpdt_tw_ffn_workspace_bytes(rows, n_model, n_ffn, code, n_chunks, True), dtype=torch.uint8, device="cuda")
+    TW.fpdt_tw_ffn_fwd(X, W1, W3, W2, Y, code, n_chunks, wb)
+    TW.fpdt_tw_ffn_bwd(X, W1, W3, W2, dY, dX, dW1, dW3, dW2, code, n_chunks, wb)
+    torch.cuda.synchronize()
+    f64 = lambda t: t.double().cpu().numpy()
+    r = np.random.default_rng(5)
+    rs = np.sort(r.choice(rows, 24, replace=False))
+    rs[0], rs[-1] = 0, rows - 1
+    ref = otw.ffn(f64(X[rs]), f64(W1), f64(W2), f64(W3), f64(dY[rs]))
+    _rowwise_ok("Y rows", f64(Y[rs]), ref["Y"])
+    _rowwise_ok("dX rows", f64(dX[rs]), ref["dX"])
+    del ref
+    fs = np.sort(r.choice(n_ffn, 12, replace=False))
+    fs[0], fs[-1] = 0, n_ffn - 1
+    ref = otw.ffn(f64(X), f64(W1[fs]), f64(W2[:, fs]), f64(W3[fs]), f64(dY))
+    _rowwise_ok("dW1 slice", f64(dW1[fs]), ref["dW1"])
+    _rowwise_ok("dW3 slice", f64(dW3[fs]), ref["dW3"])
+    _rowwise_ok("dW2 slice", f64(dW2[:, fs]).T.copy(), ref["dW2"].T.copy())
+
+
+@pytest.mark.gpu
+def test_gpu_loss_llama_vocabulary():
+    """Hidden 4096, vocabulary 128256 (Llama-3), 1024 tokens in 4 chunks, against the full oracle."""
+    rows, hidden, vocab, n_chunks = 1024, 4096, 128256, 4
+    print("[case] loss llama vocabulary", rows, hidden, vocab, n_chunks, flush=True)
+    g = torch.Generator(device="cuda").manual_seed(53)
+    H = torch.randn(rows, hidden, device="cuda", generator=g).to(torch.bfloat16)
+    W = (torch.randn(vocab, hidden, device="cuda", generator=g) * hidden ** -0.5).to(torch.bfloat16)
+    t = torch.randint(0, vocab, (rows,), device="cuda", generator=g, dtype=torch.int32)
+    loss, lse = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
+    dH = torch.empty_like(H)
+    dW = torch.zeros(vocab, hidden, device="cuda")
+    ws = torch.empty(TW.fpdt_tw_loss_workspace_bytes(rows, hidden, vocab, n_chunks), dtype=torch.uint8, device="cuda")
+    TW.fpdt_tw_loss_fwd_bwd(H, W, t, 1.0 / rows, loss, lse, dH, dW, n_chunks, ws)
+    torch.cuda.synchronize()
+    print("[step] oracle", flush=True)
+    ref = otw.cross_entropy(H.double().cpu().numpy(), W.double().cpu().numpy(), t.cpu().numpy(), grad_scale=1.0 / rows)
+    print("[step] compare", flush=True)
+    # 4096-term fp32 dot products of O(1) logits: a few 1e-5 of round-off each
+    np.testing.assert_allclose(loss.cpu().numpy(), ref["loss"], atol=1e-3)
+    np.testing.assert_allclose(lse.cpu().numpy(), ref["lse"], atol=1e-3)
+    _rowwise_ok("dH", dH.float().cpu().numpy(), ref["dH"])
+    # a vocabulary row that is nobody's target has a gradient of ~1024 probabilities of ~1e-5 each,
+    # every one rounded to bf16 before the GEMM: same relative budget per row
+    _rowwise_ok("dW", dW.cpu().numpy(), ref["dW"])
