@@ -76,3 +76,27 @@ def make_qkvdo(S, Hq, Hkv, D, dtype, seed, device="cpu"):
     V = normal("V", (S, Hkv, D), seed, dtype, device)
     dO = normal("dO", (S, Hq, D), seed, dtype, device)
     return Q, K, V, dO
+
+
+def structured(kind: str, S, Hq, Hkv, D, dtype, seed, device="cpu"):
+    """Q, K, V, dO with a score distribution that N(0,1) inputs do not produce (parity cases):
+      "rising"  scores grow by ~10 along the key axis, so the running row maximum rises in
+                nearly every key tile and the weight sits on the latest keys;
+      "offset"  all of Q and K shifted by +3: scores ~ 9 sqrt(D) with a spread of a few units;
+      "peaked"  Q and K drawn with sigma = 2.5: score spread ~6, a few keys carry each row.
+    """
+    Q, K, V, dO = (t.float() for t in make_qkvdo(S, Hq, Hkv, D, dtype, seed, device))
+    if kind == "rising":
+        ramp = torch.arange(S, device=Q.device, dtype=torch.float32) * (10.0 / S)
+        Q[:, :, 0] = float(D) ** 0.5
+        K[:, :, 0] += ramp[:, None]
+    elif kind == "offset":
+        Q += 3.0
+        K += 3.0
+    elif kind == "peaked":
+        Q *= 2.5
+        K *= 2.5
+    else:
+        raise ValueError(kind)
+    dt = torch_dtype(dtype)
+    return Q.to(dt), K.to(dt), V.to(dt), dO.to(dt)
