@@ -351,22 +351,36 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
 
     static_assert(D == 128, "fragment schedule below is laid out for D = 128");
     float pre_stat = 0.f;
-    // wave w copies fragments w, w+4, ..., w+28 of the 32 that make a step; with D = 128 every
-    // operand has 8 fragments, so the operand of fragment f0 + w is known at compile time
-    auto issue = [&](int it, u32x4* slot) {
+    // Wave w copies fragments w, w+4, ..., w+28 of the 32 that make a step; with D = 128 every
+    // operand has 8 fragments, so the operand of fragment f0 + w is known at compile time.
+    // The eight copies of a wave are NOT issued back to back: the CU's address unit takes them
+    // one at a time, and a wave whose copy is not accepted yet cannot issue its next MFMA either.
+    // issue_begin() sets up the addresses (and requests the row statistics), issue_one() sends
+    // one copy; a step calls it between its first MFMA groups.
+    uint64_t cp_src[4] = {0, 0, 0, 0};  // scalar registers: this wave's first fragment of each operand
+    const int lane16 = 16 * lane;
+    const unsigned slot_lds[2] = {lds_address(slot0) + 1024u * (unsigned)wu, lds_address(slot1) + 1024u * (unsigned)wu};
+    auto issue_begin = [&](int it) {
         const int hh = it % p.g, qb = n_qb_all - 1 - it / p.g;
         const int head = kvh * p.g + hh;
         const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
-        const u32x4* base[4] = {p.Qnat + blk * NAT_U4, p.dOnat + blk * NAT_U4, p.Qtr + blk * TR_U4,
-                                p.dOtr + blk * TR_U4};
-#pragma unroll
-        for (int f0 = 0; f0 < NFRAG; f0 += NW) {
-            const int f = f0 + wu;
-            frag_to_lds(base[f0 / 8] + (f - 8 * (f0 / 8)) * 64, slot + f * 64, lane);
-        }
+        cp_src[0] = uniform((uint64_t)(uintptr_t)(p.Qnat + blk * NAT_U4 + wu * 64));
+        cp_src[1] = uniform((uint64_t)(uintptr_t)(p.dOnat + blk * NAT_U4 + wu * 64));
+        cp_src[2] = uniform((uint64_t)(uintptr_t)(p.Qtr + blk * TR_U4 + wu * 64));
+        cp_src[3] = uniform((uint64_t)(uintptr_t)(p.dOtr + blk * TR_U4 + wu * 64));
         // raw value only: any arithmetic on it here would make the step wait for this load and,
         // the counters being in order, for every operand copy issued before it
         if (tid < 64) pre_stat = (tid < 32 ? p.LSE : p.Delta - 32)[(size_t)head * p.row_stat_stride + qb * 32 + tid];
+    };
+    // k = 0..7 (compile-time after unrolling): fragment 4 k + w of the step, i.e. fragment
+    // 4 (k % 2) + w of operand k / 2; into_slot1 is a compile-time constant at every call
+    auto issue_one = [&](int k, bool into_slot1) {
+        frag_to_lds_at(cp_src[k / 2] + 1024u * (unsigned)(NW * (k % 2)), slot_lds[into_slot1] + 1024u * (unsigned)(NW * k), lane16);
+    };
+    auto issue = [&](int it, bool into_slot1) {
+        issue_begin(it);
+#pragma unroll
+        for (int k = 0; k < NFRAG / NW; ++k) issue_one(k, into_slot1);
     };
 
     // One step.  The 32 A-operand fragments are consumed in the order Q-NAT 0..7, dO-NAT 0..7,
@@ -376,7 +390,13 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     auto step = [&](auto masked_tag, int it, const u32x4* sl, const float* st, u32x4* nslot, float* nst) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         const bool more = it + 1 < n_iter;
-        if (more) issue(it + 1, nslot);
+        // the last step copies its own operands once more into the idle slot: the copies in the
+        // MFMA sequence below then need no branch around them
+        issue_begin(more ? it + 1 : it);
+        if (MASKED) {  // diagonal steps (few): a wave may skip the arithmetic, so all copies go first
+#pragma unroll
+            for (int k = 0; k < NFRAG / NW; ++k) issue_one(k, nslot == slot1);
+        }
         const int qb = n_qb_all - 1 - it / p.g;
         const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
 
@@ -418,6 +438,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                     FPDT_MFMA_V(s1, fr[u % 6], kf[1][t]);
                 }
                 fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
+                if (!MASKED) issue_one(t, nslot == slot1);  // one operand copy of the next step per MFMA pair
                 FPDT_SCHED_FENCE();
             }
             // ---- B: dP - Delta = dO V^T - Delta, exp of S in the shadow of the MFMAs ----
@@ -504,7 +525,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     };
 
     if (n_iter > 0) {
-        issue(0, slot0);
+        issue(0, false);
         if (tid < 64) stat0[tid] = tid < 32 ? pre_stat * LOG2E : -pre_stat;
     }
     __builtin_amdgcn_s_waitcnt(0);

@@ -84,6 +84,26 @@ __device__ __forceinline__ void frag_to_lds(const u32x4* src_wave_uniform, u32x4
                  : "memory");  // m0 is reserved: the compiler sets it right before each use of its own
 }
 
+// The same copy for callers that already hold both addresses in scalar registers (values that
+// came out of uniform()): no address arithmetic in vector registers at the point of issue.
+// lds_addr is the byte address within LDS, lane16 = 16 * lane.
+__device__ __forceinline__ unsigned uniform(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ uint64_t uniform(uint64_t v)
+{
+    return ((uint64_t)uniform((unsigned)(v >> 32)) << 32) | (uint64_t)uniform((unsigned)v);
+}
+__device__ __forceinline__ unsigned lds_address(const void* p)
+{
+    return uniform((unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p);
+}
+__device__ __forceinline__ void frag_to_lds_at(uint64_t src_uniform, unsigned lds_addr_uniform, int lane16)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr_uniform), "v"(lane16), "s"(src_uniform)
+                 : "memory");
+}
+
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
 
 }  // namespace fpdt
