@@ -274,9 +274,9 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
 {
     constexpr int NW = 4, NK = 2;
     constexpr int DT = D / 16, DP = (D + 31) / 32 * 32, DB = DP / 32;
-    constexpr int NAT_U4 = DT * 64, TR_U4 = 2 * DB * 64;
-    constexpr int SLOT_U4 = 2 * NAT_U4 + 2 * TR_U4;
-    constexpr int NFRAG = 2 * DT + 4 * DB;
+    constexpr int NAT_U4 = DT * 64;
+    constexpr int SLOT_U4 = 2 * NAT_U4;  // Q block | dO block, each once (see "Operand layout" below)
+    constexpr int NFRAG = 2 * DT;
     constexpr int RING = 2;
     constexpr int BKT = NW * 32 * NK;  // keys per workgroup
     static_assert(RING == 2, "the step loops below alternate between two slots");
@@ -351,31 +351,55 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
 
     static_assert(D == 128, "fragment schedule below is laid out for D = 128");
     float pre_stat = 0.f;
-    // Wave w copies fragments w, w+4, ..., w+28 of the 32 that make a step; with D = 128 every
-    // operand has 8 fragments, so the operand of fragment f0 + w is known at compile time.
-    // The eight copies of a wave are NOT issued back to back: the CU's address unit takes them
-    // one at a time, and a wave whose copy is not accepted yet cannot issue its next MFMA either.
-    // issue_begin() sets up the addresses (and requests the row statistics), issue_one() sends
-    // one copy; a step calls it between its first MFMA groups.
-    uint64_t cp_src[4] = {0, 0, 0, 0};  // scalar registers: this wave's first fragment of each operand
-    const int lane16 = 16 * lane;
-    const unsigned slot_lds[2] = {lds_address(slot0) + 1024u * (unsigned)wu, lds_address(slot1) + 1024u * (unsigned)wu};
+    // Operand layout.  A step needs the 32 x 128 Q and dO blocks twice: as A operands contracted
+    // over d (S = Q K^T, dP = dO V^T; lane = query row, 8 consecutive d) and contracted over the
+    // query (dV^T += dO^T P, dK^T += Q^T dS; lane = d, 8 queries).  LDS holds each block ONCE, in
+    // the first form's fragment order; the second form is read with the transposing LDS load
+    // (ds_read_b64_tr_b16: each 16-lane group reads a 4-row x 16-column block of 16-bit values,
+    // lane i of the group supplying the address of row i / 4, columns 4 (i % 4) .. +3, and lane j
+    // receiving column j of the four rows).  That halves the copies and the LDS footprint of a
+    // step.  Within fragment t (16 columns of d) the 16-byte piece (h', q) = row q, columns
+    // 16 t + 8 h' .. +7 sits at position 32 h' + (q ^ 4 h' ^ 8 (t % 2)) instead of 32 h' + q: with
+    // that swizzle the 32 lanes a transposing load serves per cycle hit 32 different 8-byte bank
+    // pairs, and a plain fragment read is still a permutation of one contiguous KiB.
+    //
+    // Wave w copies fragments w, w+4, w+8, w+12 of the 16 that make a step (fragment f belongs to
+    // operand f / 8; its parity is w's).  The copy engine writes lane l's 16 bytes at position l,
+    // so lane l fetches the piece that belongs there.  The copies of a wave are NOT issued back
+    // to back: the CU's address unit takes them one at a time, and a wave whose copy is not
+    // accepted yet cannot issue its next MFMA either.  issue_begin() sets up the addresses (and
+    // requests the row statistics), issue_one() sends one copy; a step calls it between its first
+    // MFMA groups.
+    uint64_t cp_src[2] = {0, 0};  // scalar registers: this wave's first fragment of each operand
+    const int cp_lane_off = 16 * (32 * half + (col ^ (4 * half) ^ (8 * (wu & 1))));
+    const unsigned slot_addr[2] = {lds_address(slot0), lds_address(slot1)};
+    const unsigned slot_lds[2] = {slot_addr[0] + 1024u * (unsigned)wu, slot_addr[1] + 1024u * (unsigned)wu};
+    // positions of this lane's piece in an even / odd fragment (plain fragment reads)
+    const int natpos[2] = {32 * half + (col ^ (4 * half)), 32 * half + (col ^ (4 * half) ^ 8)};
+    // byte offsets of this lane's two transposing loads within a block (first / second group of
+    // four queries), to which 2048 db + 256 s2 is added for the fragment (32 db + .. d, 16 s2 + .. q)
+    int trb[2];
+    {
+        const int grp = lane >> 4, i16 = lane & 15, e = i16 >> 2, x = i16 & 3;
+        const int h = grp >> 1, dblk = grp & 1, hq = x >> 1;
+#pragma unroll
+        for (int I = 0; I < 2; ++I)
+            trb[I] = 1024 * dblk + 512 * hq + 16 * (e + 4 * (h ^ hq) + 8 * (I ^ dblk)) + 8 * (x & 1);
+    }
     auto issue_begin = [&](int it) {
         const int hh = it % p.g, qb = n_qb_all - 1 - it / p.g;
         const int head = kvh * p.g + hh;
         const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
         cp_src[0] = uniform((uint64_t)(uintptr_t)(p.Qnat + blk * NAT_U4 + wu * 64));
         cp_src[1] = uniform((uint64_t)(uintptr_t)(p.dOnat + blk * NAT_U4 + wu * 64));
-        cp_src[2] = uniform((uint64_t)(uintptr_t)(p.Qtr + blk * TR_U4 + wu * 64));
-        cp_src[3] = uniform((uint64_t)(uintptr_t)(p.dOtr + blk * TR_U4 + wu * 64));
         // raw value only: any arithmetic on it here would make the step wait for this load and,
         // the counters being in order, for every operand copy issued before it
         if (tid < 64) pre_stat = (tid < 32 ? p.LSE : p.Delta - 32)[(size_t)head * p.row_stat_stride + qb * 32 + tid];
     };
-    // k = 0..7 (compile-time after unrolling): fragment 4 k + w of the step, i.e. fragment
+    // k = 0..3 (compile-time after unrolling): fragment 4 k + w of the step, i.e. fragment
     // 4 (k % 2) + w of operand k / 2; into_slot1 is a compile-time constant at every call
     auto issue_one = [&](int k, bool into_slot1) {
-        frag_to_lds_at(cp_src[k / 2] + 1024u * (unsigned)(NW * (k % 2)), slot_lds[into_slot1] + 1024u * (unsigned)(NW * k), lane16);
+        frag_to_lds_at(cp_src[k / 2] + 1024u * (unsigned)(NW * (k % 2)), slot_lds[into_slot1] + 1024u * (unsigned)(NW * k), cp_lane_off);
     };
     auto issue = [&](int it, bool into_slot1) {
         issue_begin(it);
@@ -383,10 +407,12 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
         for (int k = 0; k < NFRAG / NW; ++k) issue_one(k, into_slot1);
     };
 
-    // One step.  The 32 A-operand fragments are consumed in the order Q-NAT 0..7, dO-NAT 0..7,
-    // dO-TR 0..7, Q-TR 0..7 (slot fragments 0..15, 24..31, 16..23); they are read from LDS four
-    // MFMA pairs ahead into a ring of six registers sets, so that a set is overwritten only
-    // two pairs after its last reader was issued.
+    // One step.  The 32 A-operand fragments are consumed in the order Q 0..7, dO 0..7 (plain),
+    // dO^T 0..7, Q^T 0..7 (transposing loads); they are read from LDS four MFMA pairs ahead into
+    // a ring of six registers sets, so that a set is overwritten only two pairs after its last
+    // reader was issued.
+    typedef short short4v __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
     auto step = [&](auto masked_tag, int it, const u32x4* sl, const float* st, u32x4* nslot, float* nst) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         const bool more = it + 1 < n_iter;
@@ -401,7 +427,20 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
         const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
 
         if (!MASKED || qpos_b0 + 31 >= kpos_w0) {  // wave-uniform
-#define FPDT_AFRAG(u_) as_bf16x8(sl[((u_) < 16 ? (u_) : (u_) < 24 ? (u_) + 8 : (u_) - 8) * 64 + lane])
+            const unsigned sl_addr = slot_addr[sl == slot1];
+            const unsigned tr0 = sl_addr + (unsigned)trb[0], tr1 = sl_addr + (unsigned)trb[1];
+            // fragment u of the stream: 0..15 plain (Q | dO), 16..23 dO^T, 24..31 Q^T
+            auto afrag = [&](int u) -> bf16x8 {
+                if (u < 16) return as_bf16x8(sl[u * 64 + natpos[u & 1]]);
+                const int i = u < 24 ? u - 16 : u - 24;
+                const unsigned o = (u < 24 ? 8192u : 0u) + 2048u * (unsigned)(i % DB) + 256u * (unsigned)(i / DB);
+                const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(tr0 + o));
+                const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(tr1 + o));
+                typedef short short8v __attribute__((ext_vector_type(8)));
+                const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                return __builtin_bit_cast(bf16x8, both);
+            };
+#define FPDT_AFRAG(u_) afrag(u_)
             bf16x8 fr[6], vb0[3], vb1[3];
 #pragma unroll
             for (int u = 0; u < 4; ++u) fr[u] = FPDT_AFRAG(u);
@@ -438,7 +477,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                     FPDT_MFMA_V(s1, fr[u % 6], kf[1][t]);
                 }
                 fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
-                if (!MASKED) issue_one(t, nslot == slot1);  // one operand copy of the next step per MFMA pair
+                if (!MASKED && t % 2 == 0) issue_one(t / 2, nslot == slot1);  // a copy for the next step every second MFMA pair
                 FPDT_SCHED_FENCE();
             }
             // ---- B: dP - Delta = dO V^T - Delta, exp of S in the shadow of the MFMAs ----
