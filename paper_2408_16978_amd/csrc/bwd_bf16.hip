@@ -625,8 +625,12 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
     constexpr int BK = 64, KB = BK / 32;
     constexpr int BQ = NWAVE * 32;
     constexpr int NAT_U4 = KB * DT * 64, TR_U4 = KB * 2 * DB * 64;  // per tile of BK keys
-    constexpr int SLOT_U4 = 2 * NAT_U4 + TR_U4;
-    constexpr int NATF = KB * DT, NFRAG = 2 * NATF + KB * 2 * DB;
+    // D = 128: the K tile is staged once; the key-contracted operand of dQ^T += K^T dS^T is read
+    // from the same block with transposing LDS loads (layout and swizzle as in the D = 128
+    // dK/dV kernel above, keys in the place of queries).  Other head dims keep the K-TR copy.
+    constexpr bool TRL = (D == 128);
+    constexpr int SLOT_U4 = 2 * NAT_U4 + (TRL ? 0 : TR_U4);
+    constexpr int NATF = KB * DT, NFRAG = 2 * NATF + (TRL ? 0 : KB * 2 * DB);
     constexpr int RING = 3;
     static_assert(RING == 3, "the tile loop below is unrolled over three slots");
     __shared__ u32x4 ring0[SLOT_U4], ring1[SLOT_U4], ring2[SLOT_U4];
@@ -650,6 +654,19 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
     const u32x4* vnb = p.Vnat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
     const u32x4* ktb = p.Ktr + (size_t)kvh * p.kv_head_stride_blocks * (2 * DB * 64);
 
+    const int cp_lane = 32 * half + (col ^ (4 * half) ^ (8 * (wu & 1)));
+    const int natpos[2] = {TRL ? 32 * half + (col ^ (4 * half)) : lane, TRL ? 32 * half + (col ^ (4 * half) ^ 8) : lane};
+    int trb[2];  // byte offsets of this lane's two transposing loads within a 32-key block
+    {
+        const int grp = lane >> 4, i16 = lane & 15, e = i16 >> 2, x = i16 & 3;
+        const int h = grp >> 1, dblk = grp & 1, hq = x >> 1;
+#pragma unroll
+        for (int I = 0; I < 2; ++I)
+            trb[I] = 1024 * dblk + 512 * hq + 16 * (e + 4 * (h ^ hq) + 8 * (I ^ dblk)) + 8 * (x & 1);
+    }
+    typedef short short4v __attribute__((ext_vector_type(4)));
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
     auto issue = [&](int it, u32x4* slot) {
 #pragma unroll
         for (int f0 = 0; f0 < NFRAG; f0 += NWAVE) {
@@ -658,7 +675,8 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
                 const u32x4* src = f < NATF ? knb + (size_t)it * NAT_U4 + f * 64
                                  : f < 2 * NATF ? vnb + (size_t)it * NAT_U4 + (f - NATF) * 64
                                                 : ktb + (size_t)it * TR_U4 + (f - 2 * NATF) * 64;
-                frag_to_lds(src, slot + f * 64, lane);
+                // a K fragment's 16-byte pieces land swizzled (the parity of fragment f0 + w is w's)
+                frag_to_lds(src, slot + f * 64, TRL && f0 < NATF ? cp_lane : lane);
             }
         }
     };
@@ -713,7 +731,8 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
     auto tile = [&](int it, const u32x4* kn, u32x4* pf_slot) {
         if (it + 2 < n_tiles) issue(it + 2, pf_slot);
         const u32x4* vn = kn + NAT_U4;
-        const u32x4* ktr = vn + NAT_U4;
+        const u32x4* ktr = vn + NAT_U4;  // (not staged when TRL)
+        const unsigned kn_addr = TRL ? lds_address(kn) : 0u;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             const int64_t key0 = p.k_pos0 + (int64_t)it * BK + 32 * kb;
@@ -724,7 +743,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
                 // fragment sets are live at a time.
                 bf16x8 kfr[DT], vfr[DT], tfr[2][DB];
 #pragma unroll
-                for (int t = 0; t < DT; ++t) kfr[t] = as_bf16x8(kn[(kb * DT + t) * 64 + lane]);
+                for (int t = 0; t < DT; ++t) kfr[t] = as_bf16x8(kn[(kb * DT + t) * 64 + natpos[t & 1]]);
                 floatx16 s, dp;
 #pragma unroll
                 for (int t = 0; t < DT; ++t) {
@@ -743,7 +762,17 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-                    for (int db = 0; db < DB; ++db) tfr[s2][db] = as_bf16x8(ktr[((kb * 2 + s2) * DB + db) * 64 + lane]);
+                    for (int db = 0; db < DB; ++db) {
+                        if constexpr (TRL) {
+                            const unsigned o = kn_addr + 16u * 64u * (unsigned)(kb * DT) + 2048u * (unsigned)db + 256u * (unsigned)s2;
+                            const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(o + (unsigned)trb[0]));
+                            const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(o + (unsigned)trb[1]));
+                            const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                            tfr[s2][db] = __builtin_bit_cast(bf16x8, both);
+                        } else {
+                            tfr[s2][db] = as_bf16x8(ktr[((kb * 2 + s2) * DB + db) * 64 + lane]);
+                        }
+                    }
                 __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], p.c, -lse2));
