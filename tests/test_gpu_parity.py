@@ -75,6 +75,21 @@ def test_bf16_pairwise_full(Hq, Hkv, D, order):
     print(parity.check_all(out, ref, True))
 
 
+@pytest.mark.parametrize("S,chunk", [(768, 256), (1280, 1280), (2304, 768)])
+@pytest.mark.parametrize("Hq,Hkv,D", [(4, 4, 128), (8, 2, 128), (4, 4, 80), (2, 1, 64)])
+def test_bf16_odd_tile_counts_and_ungrouped_heads(S, chunk, Hq, Hkv, D):
+    """Chunk and sequence lengths that are odd multiples of the 256-row tile (odd numbers of
+    steps in every kernel's unrolled loops, a single chunk, three chunks), and one query head
+    per KV head at D = 128; resident and pair-by-pair in both loop orders."""
+    announce("bf16 odd sizes", S, chunk, Hq, Hkv, D)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=8)
+    scale = D ** -0.5
+    ref = parity.oracle_full(Q, K, V, dO, scale)
+    for flags in (0, B.FPDT_PAIRWISE | B.FPDT_BWD_KV_OUTER, B.FPDT_PAIRWISE | B.FPDT_BWD_Q_OUTER):
+        out = run(Q, K, V, dO, chunk, scale, flags)
+        print(parity.check_all(out, ref, True))
+
+
 @pytest.mark.parametrize("kind", ["rising", "offset", "peaked"])
 @pytest.mark.parametrize("Hq,Hkv,D", [(4, 4, 80), (8, 2, 128)])
 def test_bf16_score_distributions_beyond_gaussian(kind, Hq, Hkv, D):
