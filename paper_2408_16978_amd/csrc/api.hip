@@ -178,13 +178,16 @@ BwdPlan plan_bwd(const Problem& p, void* ws)
         f.Delta = b.take<float>((size_t)p.Hq * p.S * 4);
     } else {
         const int64_t rows = p.fused() ? p.S : p.C;  // rows covered by the packed buffers
+        // The D = 128 kernels read the row-contracted operands (Q^T, dO^T, K^T) out of the NAT
+        // blocks with transposing LDS loads; only the other head dims need them packed as well.
+        const bool tr = p.D != 128;
         f.Qnat = b.take((size_t)(rows / 32) * p.Hq * nat_block_bytes(p.D));
-        f.Qtr = b.take((size_t)(rows / 32) * p.Hq * tr_block_bytes(p.D));
+        if (tr) f.Qtr = b.take((size_t)(rows / 32) * p.Hq * tr_block_bytes(p.D));
         f.dOnat = b.take((size_t)(rows / 32) * p.Hq * nat_block_bytes(p.D));
-        f.dOtr = b.take((size_t)(rows / 32) * p.Hq * tr_block_bytes(p.D));
+        if (tr) f.dOtr = b.take((size_t)(rows / 32) * p.Hq * tr_block_bytes(p.D));
         f.Knat = b.take((size_t)(rows / 32) * p.Hkv * nat_block_bytes(p.D));
         f.Vnat = b.take((size_t)(rows / 32) * p.Hkv * nat_block_bytes(p.D));
-        f.Ktr = b.take((size_t)(rows / 32) * p.Hkv * tr_block_bytes(p.D));
+        if (tr) f.Ktr = b.take((size_t)(rows / 32) * p.Hkv * tr_block_bytes(p.D));
         if (!p.act_host()) f.Delta = b.take<float>((size_t)p.Hq * p.S * 4);
         if (!p.fused()) {
             // accumulators: the side that the outer loop holds fixed needs one chunk, the
