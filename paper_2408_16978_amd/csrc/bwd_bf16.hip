@@ -280,7 +280,12 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     constexpr int RING = 2;
     constexpr int BKT = NW * 32 * NK;  // keys per workgroup
     static_assert(RING == 2, "the step loops below alternate between two slots");
-    __shared__ u32x4 slot0[SLOT_U4], slot1[SLOT_U4];
+    // (DP > D: the transposing loads of the padded channels reach one fragment past a block;
+    // the values land in accumulator columns that are never stored, the pad keeps them in LDS)
+    constexpr int SLOT_PAD = DP > D ? 64 : 0;
+    constexpr int UFRAG = 2 * DT + 4 * DB;  // A-operand fragments a step consumes
+    constexpr int NCOPY = (NFRAG + NW - 1) / NW;
+    __shared__ u32x4 slot0[SLOT_U4 + SLOT_PAD], slot1[SLOT_U4 + SLOT_PAD];
     __shared__ u32x4 vst[NW * NK * DT * 64];  // V NAT fragments of the workgroup's keys
     __shared__ __attribute__((aligned(16))) float stat0[64], stat1[64];  // LSE*log2e | -Delta
 
@@ -349,7 +354,6 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     if (dend > n_qb_all) dend = n_qb_all;
     const int n_hot_iter = (n_qb_all - (int)dend) * p.g;  // walked first (descending order)
 
-    static_assert(D == 128, "fragment schedule below is laid out for D = 128");
     float pre_stat = 0.f;
     // Operand layout.  A step needs the 32 x 128 Q and dO blocks twice: as A operands contracted
     // over d (S = Q K^T, dP = dO V^T; lane = query row, 8 consecutive d) and contracted over the
@@ -371,7 +375,9 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     // requests the row statistics), issue_one() sends one copy; a step calls it between its first
     // MFMA groups.
     uint64_t cp_src[2] = {0, 0};  // scalar registers: this wave's first fragment of each operand
-    const int cp_lane_off = 16 * (32 * half + (col ^ (4 * half) ^ (8 * (wu & 1))));
+    // (DT even: the parity of every fragment a wave copies is the wave's; DT odd: chosen per copy)
+    const int cp_lane_par[2] = {16 * (32 * half + (col ^ (4 * half))), 16 * (32 * half + (col ^ (4 * half) ^ 8))};
+    const int cp_lane_off = cp_lane_par[wu & 1];
     const unsigned slot_addr[2] = {lds_address(slot0), lds_address(slot1)};
     const unsigned slot_lds[2] = {slot_addr[0] + 1024u * (unsigned)wu, slot_addr[1] + 1024u * (unsigned)wu};
     // positions of this lane's piece in an even / odd fragment (plain fragment reads)
@@ -390,8 +396,9 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
         const int hh = it % p.g, qb = n_qb_all - 1 - it / p.g;
         const int head = kvh * p.g + hh;
         const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
-        cp_src[0] = uniform((uint64_t)(uintptr_t)(p.Qnat + blk * NAT_U4 + wu * 64));
-        cp_src[1] = uniform((uint64_t)(uintptr_t)(p.dOnat + blk * NAT_U4 + wu * 64));
+        const int w64 = DT == 8 ? wu * 64 : 0;  // D = 128: the wave's first fragment of each operand
+        cp_src[0] = uniform((uint64_t)(uintptr_t)(p.Qnat + blk * NAT_U4 + w64));
+        cp_src[1] = uniform((uint64_t)(uintptr_t)(p.dOnat + blk * NAT_U4 + w64));
         // raw value only: any arithmetic on it here would make the step wait for this load and,
         // the counters being in order, for every operand copy issued before it
         if (tid < 64) pre_stat = (tid < 32 ? p.LSE : p.Delta - 32)[(size_t)head * p.row_stat_stride + qb * 32 + tid];
@@ -399,12 +406,22 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     // k = 0..3 (compile-time after unrolling): fragment 4 k + w of the step, i.e. fragment
     // 4 (k % 2) + w of operand k / 2; into_slot1 is a compile-time constant at every call
     auto issue_one = [&](int k, bool into_slot1) {
-        frag_to_lds_at(cp_src[k / 2] + 1024u * (unsigned)(NW * (k % 2)), slot_lds[into_slot1] + 1024u * (unsigned)(NW * k), cp_lane_off);
+        if constexpr (DT == 8) {
+            frag_to_lds_at(cp_src[k / 2] + 1024u * (unsigned)(NW * (k % 2)), slot_lds[into_slot1] + 1024u * (unsigned)(NW * k), cp_lane_off);
+        } else {
+            // fragment f of the step (operand f / DT, its fragment f % DT); a wave without a
+            // fragment in the last round copies its previous one again (same bytes, same place)
+            int f = NW * k + wu;
+            if (f >= NFRAG) f -= NW;
+            const int op = f >= DT ? 1 : 0, t = f - op * DT;
+            const uint64_t src = (op ? cp_src[1] : cp_src[0]) + 1024u * (unsigned)t;
+            frag_to_lds_at(src, slot_addr[into_slot1] + 1024u * (unsigned)f, (t & 1) ? cp_lane_par[1] : cp_lane_par[0]);
+        }
     };
     auto issue = [&](int it, bool into_slot1) {
         issue_begin(it);
 #pragma unroll
-        for (int k = 0; k < NFRAG / NW; ++k) issue_one(k, into_slot1);
+        for (int k = 0; k < NCOPY; ++k) issue_one(k, into_slot1);
     };
 
     // One step.  The 32 A-operand fragments are consumed in the order Q 0..7, dO 0..7 (plain),
@@ -421,7 +438,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
         issue_begin(more ? it + 1 : it);
         if (MASKED) {  // diagonal steps (few): a wave may skip the arithmetic, so all copies go first
 #pragma unroll
-            for (int k = 0; k < NFRAG / NW; ++k) issue_one(k, nslot == slot1);
+            for (int k = 0; k < NCOPY; ++k) issue_one(k, nslot == slot1);
         }
         const int qb = n_qb_all - 1 - it / p.g;
         const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
@@ -431,9 +448,10 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
             const unsigned tr0 = sl_addr + (unsigned)trb[0], tr1 = sl_addr + (unsigned)trb[1];
             // fragment u of the stream: 0..15 plain (Q | dO), 16..23 dO^T, 24..31 Q^T
             auto afrag = [&](int u) -> bf16x8 {
-                if (u < 16) return as_bf16x8(sl[u * 64 + natpos[u & 1]]);
-                const int i = u < 24 ? u - 16 : u - 24;
-                const unsigned o = (u < 24 ? 8192u : 0u) + 2048u * (unsigned)(i % DB) + 256u * (unsigned)(i / DB);
+                if (u < 2 * DT) return as_bf16x8(sl[u * 64 + natpos[(u % DT) & 1]]);
+                const bool of_dO = u < 2 * DT + 2 * DB;
+                const int i = of_dO ? u - 2 * DT : u - 2 * DT - 2 * DB;
+                const unsigned o = (of_dO ? 1024u * DT : 0u) + 2048u * (unsigned)(i % DB) + 256u * (unsigned)(i / DB);
                 const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(tr0 + o));
                 const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(tr1 + o));
                 typedef short short8v __attribute__((ext_vector_type(8)));
@@ -477,15 +495,15 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                     FPDT_MFMA_V(s1, fr[u % 6], kf[1][t]);
                 }
                 fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
-                if (!MASKED && t % 2 == 0) issue_one(t / 2, nslot == slot1);  // a copy for the next step every second MFMA pair
+                if (!MASKED && t % 2 == 0 && t / 2 < NCOPY) issue_one(t / 2, nslot == slot1);  // a copy for the next step every second MFMA pair
                 FPDT_SCHED_FENCE();
             }
             // ---- B: dP - Delta = dO V^T - Delta, exp of S in the shadow of the MFMAs ----
 #pragma unroll
             for (int t = 0; t < DT; ++t) {
                 const int u = DT + t;
-                const float2 lse = stat_nx;
-                if (t + 1 < DT) stat_nx = stat2(0, 2 * t + 2);
+                float2 lse = stat_nx;
+                if (DT == 8 && t + 1 < DT) stat_nx = stat2(0, 2 * t + 2);
                 if (t == 0) {
                     FPDT_MFMA_VC(dp0, fr[u % 6], vb0[t % 3], nd);
                     FPDT_MFMA_VC(dp1, fr[u % 6], vb1[t % 3], nd);
@@ -501,7 +519,8 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                 }
                 FPDT_SCHED_FENCE();
 #pragma unroll
-                for (int r = 2 * t; r < 2 * t + 2; ++r) {
+                for (int r = 16 * t / DT; r < 16 * (t + 1) / DT; ++r) {
+                    if (DT != 8 && (r % 2 == 0 || r == 16 * t / DT)) lse = stat2(0, r & ~1);  // read at use
                     const float lse2 = (r & 1) ? lse.y : lse.x;
                     float e0 = __builtin_amdgcn_exp2f(fmaf(s0[r], p.c, -lse2));
                     float e1 = __builtin_amdgcn_exp2f(fmaf(s1[r], p.c, -lse2));
@@ -513,7 +532,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                     s0[r] = e0;
                     s1[r] = e1;
                 }
-                if (t == 3) {
+                if (16 * (t + 1) / DT >= 8 && 16 * t / DT < 8) {  // rows 0..7 are final
                     pf[0][0] = pack_half<0>(s0);
                     pf[1][0] = pack_half<0>(s1);
                 }
@@ -533,11 +552,11 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                 fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
                 FPDT_SCHED_FENCE();
 #pragma unroll
-                for (int r = 2 * i; r < 2 * i + 2; ++r) {
+                for (int r = 16 * i / (2 * DB); r < 16 * (i + 1) / (2 * DB); ++r) {
                     dp0[r] = s0[r] * dp0[r];
                     dp1[r] = s1[r] * dp1[r];
                 }
-                if (i == 3) {
+                if (16 * (i + 1) / (2 * DB) >= 8 && 16 * i / (2 * DB) < 8) {  // rows 0..7 are final
                     df[0][0] = pack_half<0>(dp0);
                     df[1][0] = pack_half<0>(dp1);
                 }
@@ -553,7 +572,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                 const int s2 = i / DB, db = i % DB;
                 FPDT_MFMA_A(dk[0][db], fr[u % 6], df[0][s2]);
                 FPDT_MFMA_A(dk[1][db], fr[u % 6], df[1][s2]);
-                if (u + 4 < 32) fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
+                if (u + 4 < UFRAG) fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
                 FPDT_SCHED_FENCE();
             }
 #undef FPDT_AFRAG
@@ -915,8 +934,8 @@ void launch_bwd_dkdv(const BwdArgs& a, hipStream_t st)
     const BwdKernelArgs k = to_kernel_args(a);
     dim3 grid((unsigned)((a.n_k / bwd_k_tile(a.D)) * a.Hkv));
     if (a.D == 128) bwd_dkdv_kernel_w4<128><<<grid, 256, 0, st>>>(k);
-    else if (a.D == 80) bwd_dkdv_kernel<80><<<grid, NTHREAD, 0, st>>>(k);
-    else bwd_dkdv_kernel<64><<<grid, NTHREAD, 0, st>>>(k);
+    else if (a.D == 80) bwd_dkdv_kernel_w4<80><<<grid, 256, 0, st>>>(k);
+    else bwd_dkdv_kernel_w4<64><<<grid, 256, 0, st>>>(k);
 }
 
 void launch_bwd_dq(const BwdArgs& a, hipStream_t st)
