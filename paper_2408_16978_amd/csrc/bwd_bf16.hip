@@ -415,7 +415,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
             if (f >= NFRAG) f -= NW;
             const int op = f >= DT ? 1 : 0, t = f - op * DT;
             const uint64_t src = (op ? cp_src[1] : cp_src[0]) + 1024u * (unsigned)t;
-            frag_to_lds_at(src, slot_addr[into_slot1] + 1024u * (unsigned)f, (t & 1) ? cp_lane_par[1] : cp_lane_par[0]);
+            frag_to_lds_at(src, slot_addr[into_slot1] + 1024u * (unsigned)f, cp_lane_par[0] ^ (128 * (t & 1)));
         }
     };
     auto issue = [&](int it, bool into_slot1) {
@@ -644,10 +644,11 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
     constexpr int BK = 64, KB = BK / 32;
     constexpr int BQ = NWAVE * 32;
     constexpr int NAT_U4 = KB * DT * 64, TR_U4 = KB * 2 * DB * 64;  // per tile of BK keys
-    // D = 128: the K tile is staged once; the key-contracted operand of dQ^T += K^T dS^T is read
-    // from the same block with transposing LDS loads (layout and swizzle as in the D = 128
-    // dK/dV kernel above, keys in the place of queries).  Other head dims keep the K-TR copy.
-    constexpr bool TRL = (D == 128);
+    // The K tile is staged once; the key-contracted operand of dQ^T += K^T dS^T is read from the
+    // same block with transposing LDS loads (layout and swizzle as in the dK/dV kernel above,
+    // keys in the place of queries).  With DP > D the loads of the padded channels reach into the
+    // next fragments of the slot; they only feed accumulator columns that are never stored.
+    constexpr bool TRL = true;
     constexpr int SLOT_U4 = 2 * NAT_U4 + (TRL ? 0 : TR_U4);
     constexpr int NATF = KB * DT, NFRAG = 2 * NATF + (TRL ? 0 : KB * 2 * DB);
     constexpr int RING = 3;
@@ -673,7 +674,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
     const u32x4* vnb = p.Vnat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
     const u32x4* ktb = p.Ktr + (size_t)kvh * p.kv_head_stride_blocks * (2 * DB * 64);
 
-    const int cp_lane = 32 * half + (col ^ (4 * half) ^ (8 * (wu & 1)));
+    const int cp_lane0 = 32 * half + (col ^ (4 * half));  // even fragment; odd: ^ 8
     const int natpos[2] = {TRL ? 32 * half + (col ^ (4 * half)) : lane, TRL ? 32 * half + (col ^ (4 * half) ^ 8) : lane};
     int trb[2];  // byte offsets of this lane's two transposing loads within a 32-key block
     {
@@ -694,8 +695,10 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
                 const u32x4* src = f < NATF ? knb + (size_t)it * NAT_U4 + f * 64
                                  : f < 2 * NATF ? vnb + (size_t)it * NAT_U4 + (f - NATF) * 64
                                                 : ktb + (size_t)it * TR_U4 + (f - 2 * NATF) * 64;
-                // a K fragment's 16-byte pieces land swizzled (the parity of fragment f0 + w is w's)
-                frag_to_lds(src, slot + f * 64, TRL && f0 < NATF ? cp_lane : lane);
+                // a K fragment's 16-byte pieces land swizzled by the parity of its index within
+                // the key block (DT even: that is the wave's parity)
+                const int par = DT % 2 == 0 ? (wu & 1) : ((f % DT) & 1);
+                frag_to_lds(src, slot + f * 64, TRL && f < NATF ? (cp_lane0 ^ (8 * par)) : lane);
             }
         }
     };
