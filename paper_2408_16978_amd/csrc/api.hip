@@ -159,8 +159,8 @@ FwdPlan plan_fwd(const Problem& p, void* ws)
 struct BwdPlan {
     float* Delta = nullptr;  // [Hq, S] (resident activations) or 2 x [Hq, C] (streamed)
     float* delta_buf[2] = {nullptr, nullptr};
-    void *Qnat = nullptr, *Qtr = nullptr, *dOnat = nullptr, *dOtr = nullptr;
-    void *Knat = nullptr, *Vnat = nullptr, *Ktr = nullptr;
+    void *Qnat = nullptr, *dOnat = nullptr;
+    void *Knat = nullptr, *Vnat = nullptr;
     float *acc_dq = nullptr, *acc_dk = nullptr, *acc_dv = nullptr;
     char* kv_raw[2] = {nullptr, nullptr};
     char* dkv_out[2] = {nullptr, nullptr};
@@ -178,16 +178,12 @@ BwdPlan plan_bwd(const Problem& p, void* ws)
         f.Delta = b.take<float>((size_t)p.Hq * p.S * 4);
     } else {
         const int64_t rows = p.fused() ? p.S : p.C;  // rows covered by the packed buffers
-        // The D = 128 kernels read the row-contracted operands (Q^T, dO^T, K^T) out of the NAT
-        // blocks with transposing LDS loads; only the other head dims need them packed as well.
-        const bool tr = p.D != 128;
+        // NAT fragments only: the backward kernels read the row-contracted operands (Q^T, dO^T,
+        // K^T) out of the NAT blocks in LDS with transposing loads
         f.Qnat = b.take((size_t)(rows / 32) * p.Hq * nat_block_bytes(p.D));
-        if (tr) f.Qtr = b.take((size_t)(rows / 32) * p.Hq * tr_block_bytes(p.D));
         f.dOnat = b.take((size_t)(rows / 32) * p.Hq * nat_block_bytes(p.D));
-        if (tr) f.dOtr = b.take((size_t)(rows / 32) * p.Hq * tr_block_bytes(p.D));
         f.Knat = b.take((size_t)(rows / 32) * p.Hkv * nat_block_bytes(p.D));
         f.Vnat = b.take((size_t)(rows / 32) * p.Hkv * nat_block_bytes(p.D));
-        if (tr) f.Ktr = b.take((size_t)(rows / 32) * p.Hkv * tr_block_bytes(p.D));
         if (!p.act_host()) f.Delta = b.take<float>((size_t)p.Hq * p.S * 4);
         if (!p.fused()) {
             // accumulators: the side that the outer loop holds fixed needs one chunk, the
@@ -561,14 +557,14 @@ int bwd_bf16_fused(const Problem& p, const void* Q, const void* K, const void* V
 {
     launch_delta(O, dO, p.S, p.Hq, p.D, 1, f.Delta, p.S, st);
     launch_delta_head(Q, dO, K, V, LSE, p.S, DELTA_HEAD_ROWS, p.Hq, p.Hkv, p.D, p.scale, f.Delta, st);
-    launch_pack(Q, p.S, p.Hq, p.D, f.Qnat, f.Qtr, p.S / 32, st);
-    launch_pack(dO, p.S, p.Hq, p.D, f.dOnat, f.dOtr, p.S / 32, st);
-    launch_pack(K, p.S, p.Hkv, p.D, f.Knat, f.Ktr, p.S / 32, st);
+    launch_pack(Q, p.S, p.Hq, p.D, f.Qnat, nullptr, p.S / 32, st);
+    launch_pack(dO, p.S, p.Hq, p.D, f.dOnat, nullptr, p.S / 32, st);
+    launch_pack(K, p.S, p.Hkv, p.D, f.Knat, nullptr, p.S / 32, st);
     launch_pack(V, p.S, p.Hkv, p.D, f.Vnat, nullptr, p.S / 32, st);
     BwdArgs a;
     a.Q = Q; a.dO = dO; a.K = K; a.V = V;
-    a.Qnat = f.Qnat; a.Qtr = f.Qtr; a.dOnat = f.dOnat; a.dOtr = f.dOtr; a.q_head_stride_blocks = p.S / 32;
-    a.Knat = f.Knat; a.Vnat = f.Vnat; a.Ktr = f.Ktr; a.kv_head_stride_blocks = p.S / 32;
+    a.Qnat = f.Qnat; a.dOnat = f.dOnat; a.q_head_stride_blocks = p.S / 32;
+    a.Knat = f.Knat; a.Vnat = f.Vnat; a.kv_head_stride_blocks = p.S / 32;
     a.LSE = LSE; a.Delta = f.Delta; a.row_stat_stride = p.S;
     a.q_pos0 = 0; a.k_pos0 = 0; a.n_q = p.S; a.n_k = p.S;
     a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
@@ -672,7 +668,7 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
                 Kj = K + (size_t)j * kvb;
                 Vj = V + (size_t)j * kvb;
             }
-            launch_pack(Kj, p.C, p.Hkv, p.D, f.Knat, f.Ktr, p.C / 32, st);
+            launch_pack(Kj, p.C, p.Hkv, p.D, f.Knat, nullptr, p.C / 32, st);
             launch_pack(Vj, p.C, p.Hkv, p.D, f.Vnat, nullptr, p.C / 32, st);
             cur_j = j;
         }
@@ -696,8 +692,8 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
                 Deltai = f.Delta + i * p.C;
                 stat_stride = p.S;
             }
-            launch_pack(Qi, p.C, p.Hq, p.D, f.Qnat, f.Qtr, p.C / 32, st);
-            launch_pack(dOi, p.C, p.Hq, p.D, f.dOnat, f.dOtr, p.C / 32, st);
+            launch_pack(Qi, p.C, p.Hq, p.D, f.Qnat, nullptr, p.C / 32, st);
+            launch_pack(dOi, p.C, p.Hq, p.D, f.dOnat, nullptr, p.C / 32, st);
             cur_i = i;
         }
         // Rows that see only a few keys get their cancellation-safe Delta: the head of the
@@ -709,8 +705,8 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
         // ---- the pair ----
         BwdArgs a;
         a.Q = Qi; a.dO = dOi; a.K = Kj; a.V = Vj;
-        a.Qnat = f.Qnat; a.Qtr = f.Qtr; a.dOnat = f.dOnat; a.dOtr = f.dOtr; a.q_head_stride_blocks = p.C / 32;
-        a.Knat = f.Knat; a.Vnat = f.Vnat; a.Ktr = f.Ktr; a.kv_head_stride_blocks = p.C / 32;
+        a.Qnat = f.Qnat; a.dOnat = f.dOnat; a.q_head_stride_blocks = p.C / 32;
+        a.Knat = f.Knat; a.Vnat = f.Vnat; a.kv_head_stride_blocks = p.C / 32;
         a.LSE = LSEi; a.Delta = Deltai; a.row_stat_stride = stat_stride;
         a.q_pos0 = i * p.C; a.k_pos0 = j * p.C; a.n_q = p.C; a.n_k = p.C;
         a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;

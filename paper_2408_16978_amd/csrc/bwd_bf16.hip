@@ -6,17 +6,18 @@
 //   dK += scale dS^T q,  dQ += scale dS k
 //
 // Two MFMA kernels, each keeping its accumulators in registers and recomputing p:
-//   bwd_dkdv_kernel : a workgroup owns 256 keys of one KV head and walks the query rows
-//       (all query heads of the group).  Scores are computed as S = Q K^T (queries are MFMA
-//       rows, keys are columns): a lane owns one key, and the register-resident p and dS
-//       tiles are the B operands of dV^T += dO^T p and dK^T += Q^T dS.
-//   bwd_dq_kernel   : a workgroup owns 256 query rows of one head and walks the keys with
-//       S^T = K Q^T (as in the forward): a lane owns one query, LSE and Delta are per-lane
-//       scalars, and dS^T is the B operand of dQ^T += K^T dS^T.
-// Operands whose contraction runs over rows arrive as TR fragments, the others as NAT
-// fragments (fpdt_internal.h).  Both kernels run 8 waves per workgroup (two per SIMD, at
-// most 256 registers each, so one wave's exp / dS arithmetic runs under the other's MFMAs)
-// and stream their operands global -> LDS directly through a small ring.
+//   bwd_dkdv_kernel_w4 : a workgroup (4 waves, one per SIMD) owns 256 keys of one KV head and
+//       walks the query rows (all query heads of the group).  Scores are computed as S = Q K^T
+//       (queries are MFMA rows, keys are columns): a lane owns one key, and the
+//       register-resident p and dS tiles are the B operands of dV^T += dO^T p and
+//       dK^T += Q^T dS.
+//   bwd_dq_kernel      : a workgroup (8 waves, two per SIMD, at most 256 registers each, so one
+//       wave's exp / dS arithmetic runs under the other's MFMAs) owns 256 query rows of one head
+//       and walks the keys with S^T = K Q^T (as in the forward): a lane owns one query, LSE and
+//       Delta are per-lane scalars, and dS^T is the B operand of dQ^T += K^T dS^T.
+// Both stream their operands global -> LDS directly through a small ring, as NAT fragments
+// (fpdt_internal.h) only: an operand whose contraction runs over rows (Q^T, dO^T, K^T) is read
+// out of the same LDS block with transposing loads.
 #include <type_traits>
 
 #include "fpdt_internal.h"
@@ -32,9 +33,9 @@ constexpr float LOG2E = 1.4426950408889634f;
 
 struct BwdKernelArgs {
     const uint16_t* Q; const uint16_t* dO; const uint16_t* K; const uint16_t* V;
-    const u32x4* Qnat; const u32x4* Qtr; const u32x4* dOnat; const u32x4* dOtr;
+    const u32x4* Qnat; const u32x4* dOnat;
     int64_t q_head_stride_blocks;
-    const u32x4* Knat; const u32x4* Vnat; const u32x4* Ktr;
+    const u32x4* Knat; const u32x4* Vnat;
     int64_t kv_head_stride_blocks;
     const float* LSE; const float* Delta; int64_t row_stat_stride;
     int64_t q_pos0, k_pos0;
@@ -62,187 +63,6 @@ __device__ __forceinline__ void store_rows_bf16(const floatx16 (&acc)[DB], float
                 *reinterpret_cast<bf16x4*>(rowp + d) = __builtin_convertvector(v, bf16x4);
             }
         }
-}
-
-// ---------------------------------------------------------------------------------------
-// dK, dV.  Wave w owns keys [k0 + 32 w, +32): its K fragments are stationary in registers,
-// its V fragments are parked in LDS.  Every step stages one 32-row query block (Q-NAT,
-// dO-NAT, Q-TR, dO-TR, LSE*log2e, Delta) in a 2-slot LDS ring, loaded one step ahead.
-template <int D>
-__global__ __launch_bounds__(NTHREAD) void bwd_dkdv_kernel(BwdKernelArgs p)
-{
-    constexpr int DT = D / 16, DP = (D + 31) / 32 * 32, DB = DP / 32;
-    constexpr int NAT_U4 = DT * 64, TR_U4 = 2 * DB * 64;
-    constexpr int SLOT_U4 = 2 * NAT_U4 + 2 * TR_U4;
-    constexpr int NFRAG = 2 * DT + 4 * DB;
-    constexpr int RING = 2;
-    constexpr int BKT = NWAVE * 32;  // keys per workgroup
-    static_assert(RING == 2, "the step loop below alternates between two slots");
-    __shared__ u32x4 slot0[SLOT_U4], slot1[SLOT_U4];
-    __shared__ u32x4 vst[NWAVE * DT * 64];  // V NAT fragments of the workgroup's keys
-    __shared__ __attribute__((aligned(16))) float stat0[64], stat1[64];  // [0,32): LSE*log2e, [32,64): -Delta of the staged block
-
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int wu = __builtin_amdgcn_readfirstlane(w);
-    const int half = lane >> 5, col = lane & 31;
-    const int kvh = blockIdx.x % p.Hkv;
-    const int kt = blockIdx.x / p.Hkv;  // ascending: earliest keys see the most queries, first
-    const int k0 = kt * BKT, kw0 = k0 + 32 * w;
-    const int64_t kpos_w0 = p.k_pos0 + kw0;
-    const int64_t kpos = kpos_w0 + col;
-
-    bf16x8 kf[DT];
-    u32x4* vmine = vst + wu * (DT * 64);
-    {
-        const size_t off = ((size_t)(kw0 + col) * p.Hkv + kvh) * D + 8 * half;
-        const u32x4* vsrc = p.Vnat + ((size_t)kvh * p.kv_head_stride_blocks + kw0 / 32) * NAT_U4;
-#pragma unroll
-        for (int t = 0; t < DT; ++t) {
-            kf[t] = as_bf16x8(*reinterpret_cast<const u32x4*>(p.K + off + 16 * t));
-            frag_to_lds(vsrc + t * 64, vmine + t * 64, lane);
-        }
-    }
-
-    floatx16 dk[DB], dv[DB];
-    const size_t wg = blockIdx.x;
-    float* adk = p.acc_dk + (wg * NWAVE + w) * (size_t)(DB * 16 * 64);
-    float* adv = p.acc_dv + (wg * NWAVE + w) * (size_t)(DB * 16 * 64);
-    if (p.flags & ACC_LOAD) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                dk[db][r] = adk[(db * 16 + r) * 64 + lane];
-                dv[db][r] = adv[(db * 16 + r) * 64 + lane];
-            }
-    } else {
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) dk[db][r] = dv[db][r] = 0.f;
-    }
-
-    // query blocks (32 rows) that can attend this key tile: position >= first key position
-    const int64_t qmin = p.k_pos0 + k0 - p.q_pos0;
-    const int qb_start = qmin > 0 ? (int)(qmin / 32) : 0;
-    const int n_qb_all = p.n_q / 32;
-    const int n_qb = n_qb_all > qb_start ? n_qb_all - qb_start : 0;
-    const int n_iter = n_qb * p.g;
-
-    float pre_stat = 0.f;
-    // Issue the loads of step `it` into ring slot `slot`: wave w copies fragments w, w+8, ...
-    // Query blocks are walked from the END of the range down to the diagonal, the heads of the
-    // group innermost: every workgroup of a launch then visits (block, head) in the same order
-    // from the same starting point and the co-resident ones stay in step, so a block fetched
-    // by one workgroup is an L2 hit for the others (walking up from each workgroup's own
-    // diagonal, or head by head, spreads them over the whole sequence: 48x refetch measured).
-    auto issue = [&](int it, u32x4* slot) {
-        const int hh = it % p.g, qb = n_qb_all - 1 - it / p.g;
-        const int head = kvh * p.g + hh;
-        const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
-#pragma unroll
-        for (int f0 = 0; f0 < NFRAG; f0 += NWAVE) {
-            const int f = f0 + wu;
-            if (f0 + NWAVE <= NFRAG || f < NFRAG) {
-                const u32x4* src = f < DT ? p.Qnat + blk * NAT_U4 + f * 64
-                                 : f < 2 * DT ? p.dOnat + blk * NAT_U4 + (f - DT) * 64
-                                 : f < 2 * DT + 2 * DB ? p.Qtr + blk * TR_U4 + (f - 2 * DT) * 64
-                                                       : p.dOtr + blk * TR_U4 + (f - 2 * DT - 2 * DB) * 64;
-                frag_to_lds(src, slot + f * 64, lane);
-            }
-        }
-        // raw value only: any arithmetic on it here would make the step wait for this load and,
-        // the counters being in order, for every operand copy issued before it
-        if (tid < 64) pre_stat = (tid < 32 ? p.LSE : p.Delta - 32)[(size_t)head * p.row_stat_stride + qb * 32 + tid];
-    };
-
-    if (n_iter > 0) {
-        issue(0, slot0);
-        if (tid < 64) stat0[tid] = tid < 32 ? pre_stat * LOG2E : -pre_stat;
-    }
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-
-    const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    // One step: compute on (qn, st), stage step it+1 into (nslot, nst).
-    auto step = [&](int it, const u32x4* qn, const float* st, u32x4* nslot, float* nst) {
-        const bool more = it + 1 < n_iter;
-        if (more) issue(it + 1, nslot);
-        const u32x4* on = qn + NAT_U4;
-        const u32x4* qt = on + NAT_U4;
-        const u32x4* ot = qt + TR_U4;
-        const int qb = n_qb_all - 1 - it / p.g;
-        const int64_t qpos_b0 = p.q_pos0 + (int64_t)qb * 32;
-
-        if (qpos_b0 + 31 >= kpos_w0) {  // wave-uniform: some query of the block reaches this wave's keys
-            // One accumulation chain at a time keeps the live registers under the 256 a wave
-            // may hold at two waves per SIMD: S -> p -> dV, then dP -> dS -> dK.
-            floatx16 s;
-#pragma unroll
-            for (int t = 0; t < DT; ++t) s = mfma32(as_bf16x8(qn[t * 64 + lane]), kf[t], t == 0 ? zero : s);
-            // p = exp2(s c - lse2), zero above the diagonal
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], p.c, -st[8 * (r >> 2) + 4 * half + (r & 3)]));
-            if (qpos_b0 < kpos_w0 + 31) {  // wave-uniform: the block straddles the diagonal
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (kpos > qpos_b0 + 8 * (r >> 2) + 4 * half + (r & 3)) s[r] = 0.f;
-            }
-            {
-                const bf16x8 pf0 = pack_half<0>(s), pf1 = pack_half<1>(s);
-                // dV^T += dO^T p
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    dv[db] = mfma32(as_bf16x8(ot[(0 * DB + db) * 64 + lane]), pf0, dv[db]);
-                    dv[db] = mfma32(as_bf16x8(ot[(1 * DB + db) * 64 + lane]), pf1, dv[db]);
-                }
-            }
-            // dP - Delta = dO V^T - Delta: the chain starts from the tile of -Delta (registers
-            // 4a .. 4a+3 hold rows 8a + 4 half + 0..3: four 16-byte reads) instead of zero, which
-            // saves a subtraction per element; dS = p (dP - Delta)
-            floatx16 dp;
-#pragma unroll
-            for (int a4 = 0; a4 < 4; ++a4) {
-                const floatx4 nd = *reinterpret_cast<const floatx4*>(st + 32 + 8 * a4 + 4 * half);
-#pragma unroll
-                for (int b = 0; b < 4; ++b) dp[4 * a4 + b] = nd[b];
-            }
-#pragma unroll
-            for (int t = 0; t < DT; ++t)
-                dp = mfma32(as_bf16x8(on[t * 64 + lane]), as_bf16x8(vmine[t * 64 + lane]), dp);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) dp[r] = s[r] * dp[r];
-            const bf16x8 df0 = pack_half<0>(dp), df1 = pack_half<1>(dp);
-            // dK^T += Q^T dS
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                dk[db] = mfma32(as_bf16x8(qt[(0 * DB + db) * 64 + lane]), df0, dk[db]);
-                dk[db] = mfma32(as_bf16x8(qt[(1 * DB + db) * 64 + lane]), df1, dk[db]);
-            }
-        }
-        if (more && tid < 64) nst[tid] = tid < 32 ? pre_stat * LOG2E : -pre_stat;
-        wait_vmem_at_most<0>();  // the direct-to-LDS loads of step it+1 have landed
-        barrier_no_fence();
-    };
-    for (int it = 0; it < n_iter; it += 2) {
-        step(it, slot0, stat0, slot1, stat1);
-        if (it + 1 < n_iter) step(it + 1, slot1, stat1, slot0, stat0);
-    }
-
-    if (p.flags & ACC_FINAL) {
-        const size_t off = ((size_t)(kw0 + col) * p.Hkv + kvh) * D;
-        store_rows_bf16<D, DB>(dk, p.scale, p.dK + off, half);
-        store_rows_bf16<D, DB>(dv, 1.f, p.dV + off, half);
-    } else {
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                adk[(db * 16 + r) * 64 + lane] = dk[db][r];
-                adv[(db * 16 + r) * 64 + lane] = dv[db][r];
-            }
-    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -643,14 +463,13 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
     constexpr int DT = D / 16, DP = (D + 31) / 32 * 32, DB = DP / 32;
     constexpr int BK = 64, KB = BK / 32;
     constexpr int BQ = NWAVE * 32;
-    constexpr int NAT_U4 = KB * DT * 64, TR_U4 = KB * 2 * DB * 64;  // per tile of BK keys
+    constexpr int NAT_U4 = KB * DT * 64;  // per tile of BK keys
     // The K tile is staged once; the key-contracted operand of dQ^T += K^T dS^T is read from the
     // same block with transposing LDS loads (layout and swizzle as in the dK/dV kernel above,
     // keys in the place of queries).  With DP > D the loads of the padded channels reach into the
     // next fragments of the slot; they only feed accumulator columns that are never stored.
-    constexpr bool TRL = true;
-    constexpr int SLOT_U4 = 2 * NAT_U4 + (TRL ? 0 : TR_U4);
-    constexpr int NATF = KB * DT, NFRAG = 2 * NATF + (TRL ? 0 : KB * 2 * DB);
+    constexpr int SLOT_U4 = 2 * NAT_U4;
+    constexpr int NATF = KB * DT, NFRAG = 2 * NATF;
     constexpr int RING = 3;
     static_assert(RING == 3, "the tile loop below is unrolled over three slots");
     __shared__ u32x4 ring0[SLOT_U4], ring1[SLOT_U4], ring2[SLOT_U4];
@@ -672,10 +491,9 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
 
     const u32x4* knb = p.Knat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
     const u32x4* vnb = p.Vnat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
-    const u32x4* ktb = p.Ktr + (size_t)kvh * p.kv_head_stride_blocks * (2 * DB * 64);
 
     const int cp_lane0 = 32 * half + (col ^ (4 * half));  // even fragment; odd: ^ 8
-    const int natpos[2] = {TRL ? 32 * half + (col ^ (4 * half)) : lane, TRL ? 32 * half + (col ^ (4 * half) ^ 8) : lane};
+    const int natpos[2] = {32 * half + (col ^ (4 * half)), 32 * half + (col ^ (4 * half) ^ 8)};
     int trb[2];  // byte offsets of this lane's two transposing loads within a 32-key block
     {
         const int grp = lane >> 4, i16 = lane & 15, e = i16 >> 2, x = i16 & 3;
@@ -692,13 +510,11 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
         for (int f0 = 0; f0 < NFRAG; f0 += NWAVE) {
             const int f = f0 + wu;
             if (f0 + NWAVE <= NFRAG || f < NFRAG) {
-                const u32x4* src = f < NATF ? knb + (size_t)it * NAT_U4 + f * 64
-                                 : f < 2 * NATF ? vnb + (size_t)it * NAT_U4 + (f - NATF) * 64
-                                                : ktb + (size_t)it * TR_U4 + (f - 2 * NATF) * 64;
+                const u32x4* src = f < NATF ? knb + (size_t)it * NAT_U4 + f * 64 : vnb + (size_t)it * NAT_U4 + (f - NATF) * 64;
                 // a K fragment's 16-byte pieces land swizzled by the parity of its index within
                 // the key block (DT even: that is the wave's parity)
                 const int par = DT % 2 == 0 ? (wu & 1) : ((f % DT) & 1);
-                frag_to_lds(src, slot + f * 64, TRL && f < NATF ? (cp_lane0 ^ (8 * par)) : lane);
+                frag_to_lds(src, slot + f * 64, f < NATF ? (cp_lane0 ^ (8 * par)) : lane);
             }
         }
     };
@@ -753,8 +569,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
     auto tile = [&](int it, const u32x4* kn, u32x4* pf_slot) {
         if (it + 2 < n_tiles) issue(it + 2, pf_slot);
         const u32x4* vn = kn + NAT_U4;
-        const u32x4* ktr = vn + NAT_U4;  // (not staged when TRL)
-        const unsigned kn_addr = TRL ? lds_address(kn) : 0u;
+        const unsigned kn_addr = lds_address(kn);
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             const int64_t key0 = p.k_pos0 + (int64_t)it * BK + 32 * kb;
@@ -785,15 +600,11 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
                 for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
                     for (int db = 0; db < DB; ++db) {
-                        if constexpr (TRL) {
-                            const unsigned o = kn_addr + 16u * 64u * (unsigned)(kb * DT) + 2048u * (unsigned)db + 256u * (unsigned)s2;
-                            const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(o + (unsigned)trb[0]));
-                            const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(o + (unsigned)trb[1]));
-                            const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                            tfr[s2][db] = __builtin_bit_cast(bf16x8, both);
-                        } else {
-                            tfr[s2][db] = as_bf16x8(ktr[((kb * 2 + s2) * DB + db) * 64 + lane]);
-                        }
+                        const unsigned o = kn_addr + 16u * 64u * (unsigned)(kb * DT) + 2048u * (unsigned)db + 256u * (unsigned)s2;
+                        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(o + (unsigned)trb[0]));
+                        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)(o + (unsigned)trb[1]));
+                        const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        tfr[s2][db] = __builtin_bit_cast(bf16x8, both);
                     }
                 __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);
 #pragma unroll
@@ -917,10 +728,10 @@ static BwdKernelArgs to_kernel_args(const BwdArgs& a)
     BwdKernelArgs k;
     k.Q = (const uint16_t*)a.Q; k.dO = (const uint16_t*)a.dO;
     k.K = (const uint16_t*)a.K; k.V = (const uint16_t*)a.V;
-    k.Qnat = (const u32x4*)a.Qnat; k.Qtr = (const u32x4*)a.Qtr;
-    k.dOnat = (const u32x4*)a.dOnat; k.dOtr = (const u32x4*)a.dOtr;
+    k.Qnat = (const u32x4*)a.Qnat;
+    k.dOnat = (const u32x4*)a.dOnat;
     k.q_head_stride_blocks = a.q_head_stride_blocks;
-    k.Knat = (const u32x4*)a.Knat; k.Vnat = (const u32x4*)a.Vnat; k.Ktr = (const u32x4*)a.Ktr;
+    k.Knat = (const u32x4*)a.Knat; k.Vnat = (const u32x4*)a.Vnat;
     k.kv_head_stride_blocks = a.kv_head_stride_blocks;
     k.LSE = a.LSE; k.Delta = a.Delta; k.row_stat_stride = a.row_stat_stride;
     k.q_pos0 = a.q_pos0; k.k_pos0 = a.k_pos0;

@@ -83,9 +83,9 @@ struct BwdArgs {
     const void* K;   // [n_k, Hkv, D]
     const void* V;   // [n_k, Hkv, D]
     // packed forms of the same ranges
-    const void* Qnat; const void* Qtr; const void* dOnat; const void* dOtr;
+    const void* Qnat; const void* dOnat;
     int64_t q_head_stride_blocks;
-    const void* Knat; const void* Vnat; const void* Ktr;
+    const void* Knat; const void* Vnat;
     int64_t kv_head_stride_blocks;
     const float* LSE;    // &LSE[0][q_pos0], head stride row_stat_stride (natural log)
     const float* Delta;  // &Delta[0][q_pos0], same stride
