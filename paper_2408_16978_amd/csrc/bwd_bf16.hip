@@ -66,11 +66,14 @@ __device__ __forceinline__ void store_rows_bf16(const floatx16 (&acc)[DB], float
 }
 
 // ---------------------------------------------------------------------------------------
-// dK, dV with 64 keys per wave (one wave per SIMD, 4 waves, 256 keys per workgroup).
+// dK, dV.  Wave w owns keys [k0 + 64 w, +64) (one wave per SIMD, 4 waves, 256 keys per
+// workgroup): its K fragments are stationary in registers, its V fragments are parked in LDS.
+// Every step stages one 32-row query block (Q, dO, LSE * log2e, -Delta) in a 2-slot LDS ring,
+// loaded one step ahead.
 //
 // A 32-key tile per wave needs one 1 KiB LDS fragment per MFMA, which LDS cannot deliver at
-// the MFMA rate; 64 keys per wave use every Q / dO fragment twice.  The 256 dK/dV accumulator
-// registers then have to live in AGPRs while the short-lived S / dP tiles must stay in
+// the MFMA rate; 64 keys per wave use every Q / dO fragment twice.  The dK/dV accumulator
+// registers (256 at D = 128) then have to live in AGPRs while the short-lived S / dP tiles must stay in
 // architectural VGPRs (VALU cannot read AGPRs): the compiler picks one form for all MFMAs of
 // a function, so the MFMAs are issued through inline assembly with explicit register classes,
 // and the wait states between an MFMA result and its first VALU reader, which the compiler
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     const int n_hot_iter = (n_qb_all - (int)dend) * p.g;  // walked first (descending order)
 
     float pre_stat = 0.f;
-    // Operand layout.  A step needs the 32 x 128 Q and dO blocks twice: as A operands contracted
+    // Operand layout.  A step needs the 32 x D Q and dO blocks twice: as A operands contracted
     // over d (S = Q K^T, dP = dO V^T; lane = query row, 8 consecutive d) and contracted over the
     // query (dV^T += dO^T P, dK^T += Q^T dS; lane = d, 8 queries).  LDS holds each block ONCE, in
     // the first form's fragment order; the second form is read with the transposing LDS load
@@ -187,9 +190,10 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     // that swizzle the 32 lanes a transposing load serves per cycle hit 32 different 8-byte bank
     // pairs, and a plain fragment read is still a permutation of one contiguous KiB.
     //
-    // Wave w copies fragments w, w+4, w+8, w+12 of the 16 that make a step (fragment f belongs to
-    // operand f / 8; its parity is w's).  The copy engine writes lane l's 16 bytes at position l,
-    // so lane l fetches the piece that belongs there.  The copies of a wave are NOT issued back
+    // Wave w copies fragments w, w+4, ... of the 2 D/16 that make a step (fragment f belongs to
+    // operand f / (D/16); at D = 128 its parity is w's and its operand is known at compile time).
+    // The copy engine writes lane l's 16 bytes at position l, so lane l fetches the piece that
+    // belongs there.  The copies of a wave are NOT issued back
     // to back: the CU's address unit takes them one at a time, and a wave whose copy is not
     // accepted yet cannot issue its next MFMA either.  issue_begin() sets up the addresses (and
     // requests the row statistics), issue_one() sends one copy; a step calls it between its first
