@@ -179,7 +179,12 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
 #pragma unroll
                 for (int r = (kb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[kb][r]), s[kb][r + 1]);
             mx = fmaxf(mx, xor32(mx));
-            const float m_new = fmaxf(m_run, mx * p.c);
+            // The running maximum is only a reference point (any value gives the same O and LSE as
+            // long as nothing overflows): it follows the true maximum only when that has risen by
+            // more than 8 (a factor 256 in the probabilities, far inside the range of bf16 and of
+            // the fp32 sums), so the rescale below is rare even while the maxima still creep up.
+            const float mc = mx * p.c;
+            const float m_new = mc > m_run + 8.f ? mc : m_run;
             // Rescale only when some query of the wave raised its maximum.
             if (__any(m_new != m_run)) {
                 const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
