@@ -25,8 +25,8 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 # only the workload it was taken on has an entry.
 HBM_TRAFFIC_PER_LAUNCH = {
     ("llama8b_2m", "fwd_sweep"): 2.79e9,
-    ("llama8b_2m", "bwd_dkdv"): 2.64e9,
-    ("llama8b_2m", "bwd_dq"): 2.92e9,
+    ("llama8b_2m", "bwd_dkdv"): 2.60e9,
+    ("llama8b_2m", "bwd_dq"): 2.91e9,
 }
 
 
