@@ -101,8 +101,8 @@ size_t fpdt_attn_workspace_bytes(int64_t S, int64_t chunk, int Hq, int Hkv, int 
  * limit).  Larger is better up to that cap: one launch of the dK/dV kernel has
  * chunk / 256 * Hkv workgroups, which fills the 256 compute units only from 32K tokens on
  * at two KV heads, and every chunk pair costs a fixed launch, state load and state store
- * (measured on the Llama-8B head share at S = 256K with K/V offloaded: 409, 645, 857, 895,
- * 889 TFLOP/s at 8K, 16K, 32K, 64K, 128K tokens; at S = 2M: 908, 877, 916 at 32K, 64K, 128K).
+ * (measured on the Llama-8B head share at S = 256K with K/V offloaded: 457, 704, 897, 927,
+ * 930 TFLOP/s at 8K, 16K, 32K, 64K, 128K tokens; at S = 2M: 933, 944, 946 at 32K, 64K, 128K).
  * Returns 0 when the arguments are invalid or no chunk fits (fpdt_last_error says which).
  * Host logic only: no device is touched.
  */
@@ -117,6 +117,9 @@ int64_t fpdt_attn_pick_chunk(int64_t S, int Hq, int Hkv, int D, int dtype, unsig
  *   Q [S,Hq,D], K, V [S,Hkv,D]  in   (device; host per the flags)
  *   O [S,Hq,D], LSE [Hq,S] fp32 out  (device; host with FPDT_ACT_ON_HOST)
  *   workspace: device memory, 256-byte aligned, >= fpdt_attn_workspace_bytes(..., 0)
+ * Stream capture: the resident schedules (no offload flag) only enqueue kernels on `stream`
+ * and may be captured in a HIP graph; with an offload flag a call on a capturing stream
+ * returns FPDT_ERR_UNSUPPORTED before anything is enqueued (the same holds for the backward).
  */
 int fpdt_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE, int64_t S,
                   int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype, unsigned flags,

@@ -253,6 +253,20 @@ int get_ctx(DeviceCtx** out)
     return FPDT_OK;
 }
 
+// The offload schedules fork onto the library's own side streams; under stream capture that
+// fork does not come back joined (the capture ends with hipErrorStreamCaptureUnjoined and leaves
+// the side streams in capture), so they are refused there.  The resident schedules only enqueue
+// kernels on the caller's stream and can be captured.
+int refuse_capture_with_offload(const Problem& p, hipStream_t st)
+{
+    if (!p.kv_host() && !p.act_host()) return FPDT_OK;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    HIP_TRY(hipStreamIsCapturing(st, &cs));
+    if (cs != hipStreamCaptureStatusNone)
+        return fail(FPDT_ERR_UNSUPPORTED, "the offload schedules cannot be captured in a HIP graph (resident ones can)");
+    return FPDT_OK;
+}
+
 // ---- pointer checks (host side, before any launch) ----
 int check_ptr(const void* ptr, size_t bytes, bool want_host, const char* name)
 {
@@ -810,6 +824,7 @@ static int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, f
     TRY(check_workspace(workspace, workspace_bytes, need));
     const FwdPlan f = plan_fwd(p, workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    TRY(refuse_capture_with_offload(p, st));
     std::lock_guard<std::mutex> lock(g_mu);
     if (!p.bf16())
         return fwd_f32(p, (const float*)Q, (const float*)K, (const float*)V, (float*)O, LSE, f, st);
@@ -863,6 +878,7 @@ static int attn_bwd_impl(const void* Q, const void* K, const void* V, const void
     TRY(check_workspace(workspace, workspace_bytes, need));
     const BwdPlan f = plan_bwd(p, workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    TRY(refuse_capture_with_offload(p, st));
     std::lock_guard<std::mutex> lock(g_mu);
     if (!p.bf16())
         return bwd_f32(p, (const float*)Q, (const float*)K, (const float*)V, (const float*)O, LSE,
