@@ -117,9 +117,10 @@ int64_t fpdt_attn_pick_chunk(int64_t S, int Hq, int Hkv, int D, int dtype, unsig
  *   Q [S,Hq,D], K, V [S,Hkv,D]  in   (device; host per the flags)
  *   O [S,Hq,D], LSE [Hq,S] fp32 out  (device; host with FPDT_ACT_ON_HOST)
  *   workspace: device memory, 256-byte aligned, >= fpdt_attn_workspace_bytes(..., 0)
- * Stream capture: the resident schedules (no offload flag) only enqueue kernels on `stream`
- * and may be captured in a HIP graph; with an offload flag a call on a capturing stream
- * returns FPDT_ERR_UNSUPPORTED before anything is enqueued (the same holds for the backward).
+ * Stream capture: forward and backward only enqueue kernels, copies and event waits (the
+ * offload schedules fork onto the library's side streams and join back through events), so
+ * they may be captured in a HIP graph; the tensors and the workspace, host buffers included,
+ * must then stay valid for every replay.
  */
 int fpdt_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE, int64_t S,
                   int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype, unsigned flags,

@@ -253,19 +253,29 @@ int get_ctx(DeviceCtx** out)
     return FPDT_OK;
 }
 
-// The offload schedules fork onto the library's own side streams; under stream capture that
-// fork does not come back joined (the capture ends with hipErrorStreamCaptureUnjoined and leaves
-// the side streams in capture), so they are refused there.  The resident schedules only enqueue
-// kernels on the caller's stream and can be captured.
-int refuse_capture_with_offload(const Problem& p, hipStream_t st)
-{
-    if (!p.kv_host() && !p.act_host()) return FPDT_OK;
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    HIP_TRY(hipStreamIsCapturing(st, &cs));
-    if (cs != hipStreamCaptureStatusNone)
-        return fail(FPDT_ERR_UNSUPPORTED, "the offload schedules cannot be captured in a HIP graph (resident ones can)");
-    return FPDT_OK;
-}
+// Event bookkeeping of one call.  The schedules wait for "buffer free" / "copied out" events
+// before they reuse a staging buffer; the first use of a buffer in a call has no such event yet
+// (every buffer is free when a call starts: the call's fork orders it behind the stream's
+// earlier work), and waiting there for the event's last record, which belongs to an EARLIER call,
+// is not only pointless: under stream capture it is an error (a dependency on uncaptured work).
+// So a wait is issued only for events this call has recorded.
+struct CallEvents {
+    DeviceCtx* c = nullptr;
+    uint32_t seen = 0;
+    static_assert(EV_COUNT <= 32, "one bit per event");
+    int record(int e, hipStream_t s)
+    {
+        HIP_TRY(hipEventRecord(c->ev[e], s));
+        seen |= 1u << e;
+        return FPDT_OK;
+    }
+    int wait(hipStream_t s, int e)
+    {
+        if (!(seen & (1u << e))) return FPDT_OK;
+        HIP_TRY(hipStreamWaitEvent(s, c->ev[e], 0));
+        return FPDT_OK;
+    }
+};
 
 // ---- pointer checks (host side, before any launch) ----
 int check_ptr(const void* ptr, size_t bytes, bool want_host, const char* name)
@@ -436,11 +446,13 @@ int fwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
 {
     const bool kvh = p.kv_host(), acth = p.act_host();
     DeviceCtx* c = nullptr;
+    CallEvents ev;
     if (kvh || acth) {
         TRY(get_ctx(&c));
-        HIP_TRY(hipEventRecord(c->ev[EV_FORK], st));
-        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_FORK], 0));
-        HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_FORK], 0));
+        ev.c = c;
+        TRY(ev.record(EV_FORK, st));
+        TRY(ev.wait(c->h2d, EV_FORK));
+        TRY(ev.wait(c->d2h, EV_FORK));
     }
     const size_t kvb = p.kv_chunk_bytes(), qb = p.q_chunk_bytes();
 
@@ -451,17 +463,17 @@ int fwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
             if (p.on(m, i)) kv_seq.push_back(i);
     auto fetch_kv = [&](size_t t) -> int {
         const int b = (int)(t & 1);
-        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_KV_FREE0 + b], 0));
+        TRY(ev.wait(c->h2d, EV_KV_FREE0 + b));
         TRY(copy_h2d(f.kv_raw[b], K + (size_t)kv_seq[t] * kvb, kvb, c->h2d));
         TRY(copy_h2d(f.kv_raw[b] + kvb, V + (size_t)kv_seq[t] * kvb, kvb, c->h2d));
-        HIP_TRY(hipEventRecord(c->ev[EV_KV_READY0 + b], c->h2d));
+        TRY(ev.record(EV_KV_READY0 + b, c->h2d));
         return FPDT_OK;
     };
     auto fetch_q = [&](int64_t m) -> int {
         const int b = (int)(m & 1);
-        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_ACT_FREE0 + b], 0));
+        TRY(ev.wait(c->h2d, EV_ACT_FREE0 + b));
         TRY(copy_h2d(f.q_buf[b], Q + (size_t)m * qb, qb, c->h2d));
-        HIP_TRY(hipEventRecord(c->ev[EV_ACT_READY0 + b], c->h2d));
+        TRY(ev.record(EV_ACT_READY0 + b, c->h2d));
         return FPDT_OK;
     };
 
@@ -476,7 +488,7 @@ int fwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
         int64_t lse_stride = p.S;
         if (acth) {
             if (m + 1 < p.u) TRY(fetch_q(m + 1));
-            HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_ACT_READY0 + qbuf], 0));
+            TRY(ev.wait(st, EV_ACT_READY0 + qbuf));
             Qm = f.q_buf[qbuf];
             Om = f.o_buf[qbuf];
             LSEm = f.lse_buf[qbuf];
@@ -489,15 +501,15 @@ int fwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
             if (kvh) {
                 const int b = (int)(t & 1);
                 if (t + 1 < kv_seq.size()) TRY(fetch_kv(t + 1));
-                HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_KV_READY0 + b], 0));
+                TRY(ev.wait(st, EV_KV_READY0 + b));
                 Ki = f.kv_raw[b];
                 Vi = f.kv_raw[b] + kvb;
             }
             launch_pack(Ki, p.C, p.Hkv, p.D, f.Knat, nullptr, p.C / 32, st);
             launch_pack(Vi, p.C, p.Hkv, p.D, nullptr, f.Vtr, p.C / 32, st);
-            if (kvh) HIP_TRY(hipEventRecord(c->ev[EV_KV_FREE0 + (int)(t & 1)], st));
+            if (kvh) TRY(ev.record(EV_KV_FREE0 + (int)(t & 1), st));
             if (acth && i == m)  // the finalising sweep overwrites the staging O / LSE chunk
-                HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_OUT_COPIED0 + qbuf], 0));
+                TRY(ev.wait(st, EV_OUT_COPIED0 + qbuf));
             FwdArgs a;
             a.Q = Qm; a.Knat = f.Knat; a.Vtr = f.Vtr; a.kv_head_stride_blocks = p.C / 32;
             a.O = Om; a.LSE = LSEm; a.lse_stride = lse_stride;
@@ -509,21 +521,21 @@ int fwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
             ++t;
         }
         if (acth) {
-            HIP_TRY(hipEventRecord(c->ev[EV_ACT_FREE0 + qbuf], st));
-            HIP_TRY(hipEventRecord(c->ev[EV_OUT_DONE0 + qbuf], st));
-            HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_OUT_DONE0 + qbuf], 0));
+            TRY(ev.record(EV_ACT_FREE0 + qbuf, st));
+            TRY(ev.record(EV_OUT_DONE0 + qbuf, st));
+            TRY(ev.wait(c->d2h, EV_OUT_DONE0 + qbuf));
             TRY(copy_d2h(O + (size_t)m * qb, f.o_buf[qbuf], qb, c->d2h));
             HIP_TRY(hipMemcpy2DAsync(LSE + m * p.C, (size_t)p.S * 4, f.lse_buf[qbuf], (size_t)p.C * 4,
                                      (size_t)p.C * 4, (size_t)p.Hq, hipMemcpyDeviceToHost, c->d2h));
             g_d2h_bytes += (size_t)p.C * 4 * p.Hq;
-            HIP_TRY(hipEventRecord(c->ev[EV_OUT_COPIED0 + qbuf], c->d2h));
+            TRY(ev.record(EV_OUT_COPIED0 + qbuf, c->d2h));
         }
     }
     if (c) {
-        HIP_TRY(hipEventRecord(c->ev[EV_JOIN_H2D], c->h2d));
-        HIP_TRY(hipEventRecord(c->ev[EV_JOIN_D2H], c->d2h));
-        HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_JOIN_H2D], 0));
-        HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_JOIN_D2H], 0));
+        TRY(ev.record(EV_JOIN_H2D, c->h2d));
+        TRY(ev.record(EV_JOIN_D2H, c->d2h));
+        TRY(ev.wait(st, EV_JOIN_H2D));
+        TRY(ev.wait(st, EV_JOIN_D2H));
     }
     return launch_status("bf16 pairwise forward");
 }
@@ -600,11 +612,13 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
 {
     const bool kvh = p.kv_host(), acth = p.act_host(), qo = p.q_outer();
     DeviceCtx* c = nullptr;
+    CallEvents ev;
     if (kvh || acth) {
         TRY(get_ctx(&c));
-        HIP_TRY(hipEventRecord(c->ev[EV_FORK], st));
-        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_FORK], 0));
-        HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_FORK], 0));
+        ev.c = c;
+        TRY(ev.record(EV_FORK, st));
+        TRY(ev.wait(c->h2d, EV_FORK));
+        TRY(ev.wait(c->d2h, EV_FORK));
     }
     const size_t kvb = p.kv_chunk_bytes(), qb = p.q_chunk_bytes();
     const size_t acc_q_chunk = bwd_acc_dq_bytes(p.C, p.Hq, p.D) / 4;     // floats per chunk slot
@@ -630,23 +644,23 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
 
     auto fetch_kv = [&](size_t n) -> int {
         const int b = (int)(n & 1);
-        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_KV_FREE0 + b], 0));
+        TRY(ev.wait(c->h2d, EV_KV_FREE0 + b));
         TRY(copy_h2d(f.kv_raw[b], K + (size_t)kv_seq[n] * kvb, kvb, c->h2d));
         TRY(copy_h2d(f.kv_raw[b] + kvb, V + (size_t)kv_seq[n] * kvb, kvb, c->h2d));
-        HIP_TRY(hipEventRecord(c->ev[EV_KV_READY0 + b], c->h2d));
+        TRY(ev.record(EV_KV_READY0 + b, c->h2d));
         return FPDT_OK;
     };
     // activations (Q-outer only): Q_i, dO_i, O_i and the LSE strip of chunk i
     auto fetch_act = [&](int64_t i) -> int {
         const int b = (int)(i & 1);
-        HIP_TRY(hipStreamWaitEvent(c->h2d, c->ev[EV_ACT_FREE0 + b], 0));
+        TRY(ev.wait(c->h2d, EV_ACT_FREE0 + b));
         TRY(copy_h2d(f.act_raw[b], Q + (size_t)i * qb, qb, c->h2d));
         TRY(copy_h2d(f.act_raw[b] + qb, dO + (size_t)i * qb, qb, c->h2d));
         TRY(copy_h2d(f.act_raw[b] + 2 * qb, O + (size_t)i * qb, qb, c->h2d));
         HIP_TRY(hipMemcpy2DAsync(f.lse_buf[b], (size_t)p.C * 4, LSE + i * p.C, (size_t)p.S * 4,
                                  (size_t)p.C * 4, (size_t)p.Hq, hipMemcpyHostToDevice, c->h2d));
         g_h2d_bytes += (size_t)p.C * 4 * p.Hq;
-        HIP_TRY(hipEventRecord(c->ev[EV_ACT_READY0 + b], c->h2d));
+        TRY(ev.record(EV_ACT_READY0 + b, c->h2d));
         return FPDT_OK;
     };
 
@@ -670,12 +684,12 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
         if (j != cur_j) {
             if (kvh) {
                 if (cur_j >= 0) {  // previous staged chunk no longer read by any kernel
-                    HIP_TRY(hipEventRecord(c->ev[EV_KV_FREE0 + (int)(kv_n & 1)], st));
+                    TRY(ev.record(EV_KV_FREE0 + (int)(kv_n & 1), st));
                     ++kv_n;
                 }
                 if (kv_n + 1 < kv_seq.size()) TRY(fetch_kv(kv_n + 1));
                 const int b = (int)(kv_n & 1);
-                HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_KV_READY0 + b], 0));
+                TRY(ev.wait(st, EV_KV_READY0 + b));
                 Kj = f.kv_raw[b];
                 Vj = f.kv_raw[b] + kvb;
             } else {
@@ -689,10 +703,10 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
         // ---- query side ----
         if (i != cur_i) {
             if (acth) {
-                if (cur_i >= 0) HIP_TRY(hipEventRecord(c->ev[EV_ACT_FREE0 + (int)(cur_i & 1)], st));
+                if (cur_i >= 0) TRY(ev.record(EV_ACT_FREE0 + (int)(cur_i & 1), st));
                 if (i + 1 < p.u) TRY(fetch_act(i + 1));
                 const int b = (int)(i & 1);
-                HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_ACT_READY0 + b], 0));
+                TRY(ev.wait(st, EV_ACT_READY0 + b));
                 Qi = f.act_raw[b];
                 dOi = f.act_raw[b] + qb;
                 launch_delta(f.act_raw[b] + 2 * qb, dOi, p.C, p.Hq, p.D, 1, f.delta_buf[b], p.C, st);
@@ -733,31 +747,31 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
         a.dQ = acth ? f.dq_out[ob_q] : dQ + (size_t)i * qb;
 
         a.flags = (first_for_kv ? 0 : ACC_LOAD) | (last_for_kv ? ACC_FINAL : 0);
-        if (kvh && last_for_kv) HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_DKV_COPIED0 + ob_kv], 0));
+        if (kvh && last_for_kv) TRY(ev.wait(st, EV_DKV_COPIED0 + ob_kv));
         { PROF(FPDT_PROF_DKDV, st); launch_bwd_dkdv(a, st); }
         if (kvh && last_for_kv) {
-            HIP_TRY(hipEventRecord(c->ev[EV_DKV_DONE0 + ob_kv], st));
-            HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_DKV_DONE0 + ob_kv], 0));
+            TRY(ev.record(EV_DKV_DONE0 + ob_kv, st));
+            TRY(ev.wait(c->d2h, EV_DKV_DONE0 + ob_kv));
             TRY(copy_d2h(dK + (size_t)j * kvb, f.dkv_out[ob_kv], kvb, c->d2h));
             TRY(copy_d2h(dV + (size_t)j * kvb, f.dkv_out[ob_kv] + kvb, kvb, c->d2h));
-            HIP_TRY(hipEventRecord(c->ev[EV_DKV_COPIED0 + ob_kv], c->d2h));
+            TRY(ev.record(EV_DKV_COPIED0 + ob_kv, c->d2h));
         }
 
         a.flags = (first_for_q ? 0 : ACC_LOAD) | (last_for_q ? ACC_FINAL : 0);
-        if (acth && last_for_q) HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_OUT_COPIED0 + ob_q], 0));
+        if (acth && last_for_q) TRY(ev.wait(st, EV_OUT_COPIED0 + ob_q));
         { PROF(FPDT_PROF_DQ, st); launch_bwd_dq(a, st); }
         if (acth && last_for_q) {
-            HIP_TRY(hipEventRecord(c->ev[EV_OUT_DONE0 + ob_q], st));
-            HIP_TRY(hipStreamWaitEvent(c->d2h, c->ev[EV_OUT_DONE0 + ob_q], 0));
+            TRY(ev.record(EV_OUT_DONE0 + ob_q, st));
+            TRY(ev.wait(c->d2h, EV_OUT_DONE0 + ob_q));
             TRY(copy_d2h(dQ + (size_t)i * qb, f.dq_out[ob_q], qb, c->d2h));
-            HIP_TRY(hipEventRecord(c->ev[EV_OUT_COPIED0 + ob_q], c->d2h));
+            TRY(ev.record(EV_OUT_COPIED0 + ob_q, c->d2h));
         }
     }
     if (c) {
-        HIP_TRY(hipEventRecord(c->ev[EV_JOIN_H2D], c->h2d));
-        HIP_TRY(hipEventRecord(c->ev[EV_JOIN_D2H], c->d2h));
-        HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_JOIN_H2D], 0));
-        HIP_TRY(hipStreamWaitEvent(st, c->ev[EV_JOIN_D2H], 0));
+        TRY(ev.record(EV_JOIN_H2D, c->h2d));
+        TRY(ev.record(EV_JOIN_D2H, c->d2h));
+        TRY(ev.wait(st, EV_JOIN_H2D));
+        TRY(ev.wait(st, EV_JOIN_D2H));
     }
     return launch_status("bf16 pairwise backward");
 }
@@ -824,7 +838,6 @@ static int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, f
     TRY(check_workspace(workspace, workspace_bytes, need));
     const FwdPlan f = plan_fwd(p, workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    TRY(refuse_capture_with_offload(p, st));
     std::lock_guard<std::mutex> lock(g_mu);
     if (!p.bf16())
         return fwd_f32(p, (const float*)Q, (const float*)K, (const float*)V, (float*)O, LSE, f, st);
@@ -878,7 +891,6 @@ static int attn_bwd_impl(const void* Q, const void* K, const void* V, const void
     TRY(check_workspace(workspace, workspace_bytes, need));
     const BwdPlan f = plan_bwd(p, workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    TRY(refuse_capture_with_offload(p, st));
     std::lock_guard<std::mutex> lock(g_mu);
     if (!p.bf16())
         return bwd_f32(p, (const float*)Q, (const float*)K, (const float*)V, (const float*)O, LSE,
