@@ -356,3 +356,52 @@ def test_gpu_loss_llama_vocabulary():
     # a vocabulary row that is nobody's target has a gradient of ~1024 probabilities of ~1e-5 each,
     # every one rounded to bf16 before the GEMM: same relative budget per row
     _rowwise_ok("dW", dW.cpu().numpy(), ref["dW"])
+
+
+@pytest.mark.gpu
+def test_gpu_tokenwise_calls_replay_from_a_graph():
+    """FFN forward + backward and the fused loss captured in one HIP graph (library GEMMs and the
+    row / activation kernels on the captured stream), replayed three times with eager work in
+    between; every replay equals the eager result bit for bit."""
+    rows, n_model, n_ffn, vocab, n_chunks = 1024, 256, 688, 1536, 4
+    print("[case] token-wise graph", rows, n_model, n_ffn, vocab, flush=True)
+    g = torch.Generator(device="cuda").manual_seed(61)
+    bf = lambda *s, std=1.0: (torch.randn(*s, device="cuda", generator=g) * std).to(torch.bfloat16)
+    X, dY = bf(rows, n_model), bf(rows, n_model)
+    W1, W3, W2 = bf(n_ffn, n_model, std=n_model ** -0.5), bf(n_ffn, n_model, std=n_model ** -0.5), bf(n_model, n_ffn, std=n_ffn ** -0.5)
+    Wv = bf(vocab, n_model, std=n_model ** -0.5)
+    tgt = torch.randint(0, vocab, (rows,), device="cuda", generator=g, dtype=torch.int32)
+    code = TW.FPDT_TW_SWIGLU
+    Y, dX, dH = torch.empty_like(X), torch.empty_like(X), torch.empty_like(X)
+    dW1, dW3, dW2 = (torch.zeros_like(w, dtype=torch.float32) for w in (W1, W3, W2))
+    dWv = torch.zeros_like(Wv, dtype=torch.float32)
+    loss, lse = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
+    wb = torch.empty(TW.fpdt_tw_ffn_workspace_bytes(rows, n_model, n_ffn, code, n_chunks, True), dtype=torch.uint8, device="cuda")
+    wl = torch.empty(TW.fpdt_tw_loss_workspace_bytes(rows, n_model, vocab, n_chunks), dtype=torch.uint8, device="cuda")
+
+    def step():
+        TW.fpdt_tw_ffn_fwd(X, W1, W3, W2, Y, code, n_chunks, wb)
+        TW.fpdt_tw_ffn_bwd(X, W1, W3, W2, dY, dX, dW1, dW3, dW2, code, n_chunks, wb)
+        TW.fpdt_tw_loss_fwd_bwd(Y, Wv, tgt, 1.0 / rows, loss, lse, dH, dWv, n_chunks, wl)
+
+    outs = {"Y": Y, "dX": dX, "dH": dH, "dW1": dW1, "dW3": dW3, "dW2": dW2, "dWv": dWv, "loss": loss, "lse": lse}
+
+    def reset():  # written outputs are poisoned, accumulated-into ones start from zero
+        for n, t in outs.items():
+            t.zero_() if n.startswith("dW") else t.fill_(float("nan"))
+
+    step()  # first call: creates the rocBLAS handle and loads its kernels outside any capture
+    reset()
+    step()
+    torch.cuda.synchronize()
+    want = {n: t.clone() for n, t in outs.items()}
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr, stream=torch.cuda.Stream()):
+        step()
+    for rep in range(3):
+        reset()
+        torch.cuda.synchronize()
+        gr.replay()
+        torch.cuda.synchronize()
+        for n, t in outs.items():
+            assert torch.equal(t.view(torch.uint8), want[n].view(torch.uint8)), (n, rep)
