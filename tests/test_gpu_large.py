@@ -117,3 +117,44 @@ def test_uniform_average_closed_form_at_256k():
     ref = mean.repeat_interleave(Hq // Hkv, dim=1)
     idx = torch.arange(0, S, 997, device="cuda")
     parity.check("O", b.O[idx], ref[idx].cpu().numpy(), True)
+
+
+def test_blocksparse_256k_kv_offloaded_sampled():
+    """Block-sparse K/V fetch (Sec. 5.5) at the Llama-8B head share, S = 256K in 8 chunks of 32K,
+    K/V in pinned host memory, a seeded mask that keeps about half of the below-diagonal pairs:
+    sampled query rows and the tail window of keys against the masked oracle."""
+    S, chunk, Hq, Hkv, D = 262144, 32768, 8, 2, 128
+    u, scale, tail = S // chunk, D ** -0.5, 32
+    mask = np.tril(np.random.default_rng(21).random((u, u)) < 0.5)
+    np.fill_diagonal(mask, True)
+    mask[5, :5] = False  # one query chunk that keeps only its diagonal
+    print("[case] block-sparse 256K, kept pairs", int(mask.sum()), "of", u * (u + 1) // 2, flush=True)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", 23, device="cuda")
+    b = runner.make_buffers(Q, K, V, dO, chunk, scale, B.FPDT_KV_ON_HOST, chunk_mask=mask)
+    runner.forward(b)
+    runner.backward(b)
+    torch.cuda.synchronize()
+    h2d, _ = B.fpdt_last_link_bytes()
+    print("[gpu done] backward fetched", h2d / 2 ** 20, "MiB", flush=True)
+
+    rows = {0, 1, 255, 256, S - 1, S - 2}
+    for m in range(1, u):
+        rows |= {m * chunk - 1, m * chunk, m * chunk + 1, m * chunk + 255, m * chunk + 256}
+    rows |= set(int(x) for x in np.random.default_rng(22).integers(0, S, size=24))
+    rows = np.array(sorted(rows), dtype=np.int64)
+    ridx = torch.from_numpy(rows).cuda()
+    K64, V64 = parity.to64(K), parity.to64(V)
+    ref = definition.rows(parity.to64(Q[ridx]), K64, V64, rows, scale, dOr=parity.to64(dO[ridx]),
+                          chunk=chunk, chunk_mask=mask)
+    print("O", parity.check("O", b.O[ridx], ref["O"], True),
+          "LSE", parity.check("LSE", b.LSE[:, ridx], ref["LSE"], True),
+          "dQ", parity.check("dQ", b.dQ[ridx], ref["dQ"], True), flush=True)
+    # the last `tail` keys are reached by the last `tail` queries only (their chunk's diagonal pair)
+    idx = np.arange(S - tail, S)
+    Qw, dOw = parity.to64(Q[S - tail:]), parity.to64(dO[S - tail:])
+    r = definition.rows(Qw, K64, V64, idx, scale, dOr=dOw, chunk=chunk, chunk_mask=mask)
+    dK, dV = definition.cols(Qw, dOw, r["LSE"], r["Delta"], S - tail, K64[S - tail:], V64[S - tail:], idx, S,
+                             scale, chunk=chunk, chunk_mask=mask)
+    print("dK", parity.check("dK", b.dK[S - tail:], dK, True), "dV", parity.check("dV", b.dV[S - tail:], dV, True), flush=True)
+    for n in ("O", "LSE", "dQ", "dK", "dV"):
+        assert torch.isfinite(getattr(b, n)).all(), n
