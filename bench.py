@@ -13,21 +13,38 @@ import os
 import sys
 import time
 
+T_START = time.perf_counter()
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 
-# HBM bytes (read + written) per launch of each kernel, from two rocprofv3 --pmc runs of this
-# script (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the plain
-# 1 GiB copy kernel of --calibrate-copy (2.0 and 1.0).  A profiler measurement, not a live one:
-# only the workload it was taken on has an entry.
-HBM_TRAFFIC_PER_LAUNCH = {
-    ("llama8b_2m", "fwd_sweep"): 2.79e9,
-    ("llama8b_2m", "bwd_dkdv"): 2.60e9,
-    ("llama8b_2m", "bwd_dq"): 2.91e9,
-}
+# Wall-clock budgets (seconds).  One pass of the default workload takes about half a minute, so
+# the number of timed passes is min(--steps, what fits in TIMED_BUDGET_S), at least one; the
+# whole run (import, input generation, warm-up, timed passes, link probe, oracle baseline) is
+# meant to stay far inside a ten-minute limit.
+TIMED_BUDGET_S = 105.0
+WARMUP_BUDGET_S = 20.0
+
+
+def hbm_traffic_per_launch(workload, kernel):
+    """HBM bytes (read + written) per launch of `kernel`, from the tracked rocprofv3 --pmc summary
+    of this workload (FETCH_SIZE and WRITE_SIZE runs, each scaled by what the same counter reads
+    for the plain 1 GiB copy kernel of --calibrate-copy).  A profiler measurement, not a live one:
+    None for a workload that has no such summary."""
+    path = os.path.join(ROOT, "profiles", "attn_kernels_%s_hbm_traffic.txt" % workload)
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch"):
+                    for item in line.split()[1:]:
+                        k, _, v = item.partition("=")
+                        if k == kernel:
+                            return float(v)
+    except OSError:
+        pass
+    return None
 
 
 def parse():
@@ -43,6 +60,9 @@ def parse():
     ap.add_argument("--keep", type=float, default=None,
                     help="block-sparse attention (Sec. 5.5): keep each below-diagonal chunk pair "
                          "with this probability (seeded), always keep the diagonal")
+    ap.add_argument("--time-budget", type=float, default=TIMED_BUDGET_S,
+                    help="seconds of timed passes: fewer than --steps are timed if they do not fit "
+                         "(never fewer than one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-link-probe", action="store_true")
     ap.add_argument("--resident-compare", action="store_true",
@@ -154,19 +174,45 @@ def main():
         torch.cuda.synchronize()
         del w, wb
 
-    def step():
-        runner.forward(bufs)
-        runner.backward(bufs)
-
+    # Warm-up passes run the same kernels, chunk size, residency and copy pipeline on a PREFIX of
+    # the workload (at most four chunks): a full pass of the default workload takes half a minute
+    # and adds nothing that the prefix does not already warm (code objects, side streams, events,
+    # pinned pages, clocks).  Workloads that take well under a second are warmed up in full.
+    warm_S = cfg.S if cfg.S <= 262144 else 4 * cfg.chunk
+    if warm_S == cfg.S:
+        wbufs = bufs
+    else:
+        nc = warm_S // cfg.chunk
+        dt = B.FPDT_DTYPE_BF16 if cfg.dtype == "bf16" else B.FPDT_DTYPE_F32
+        fwd_flags = bufs.flags & ~(B.FPDT_BWD_KV_OUTER | B.FPDT_BWD_Q_OUTER)
+        wbufs = runner.Buffers(
+            Q=bufs.Q[:warm_S], K=bufs.K[:warm_S], V=bufs.V[:warm_S], dO=bufs.dO[:warm_S],
+            O=bufs.O[:warm_S], dQ=bufs.dQ[:warm_S], dK=bufs.dK[:warm_S], dV=bufs.dV[:warm_S],
+            LSE=torch.empty((cfg.Hq, warm_S), dtype=torch.float32, device=bufs.LSE.device,
+                            pin_memory=bufs.LSE.is_pinned()),
+            ws_fwd=B.alloc_workspace(warm_S, cfg.chunk, cfg.Hq, cfg.Hkv, cfg.D, dt, fwd_flags, False),
+            ws_bwd=B.alloc_workspace(warm_S, cfg.chunk, cfg.Hq, cfg.Hkv, cfg.D, dt, bufs.flags, True),
+            chunk=cfg.chunk, scale=cfg.scale, flags=bufs.flags,
+            chunk_mask=mask[:nc, :nc].copy() if mask is not None else None)
+    warm_done = 0
+    tw = time.perf_counter()
     for _ in range(args.warmup):
-        step()
+        runner.forward(wbufs)
+        runner.backward(wbufs)
+        torch.cuda.synchronize()
+        warm_done += 1
+        if time.perf_counter() - tw > WARMUP_BUDGET_S:
+            break
+    if wbufs is not bufs:
+        del wbufs
     torch.cuda.synchronize()
 
     B.fpdt_profile_enable(True)
     fwd_ms = bwd_ms = 0.0
     link = [0, 0]
+    steps_done = 0
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    while steps_done < args.steps:
         ta = time.perf_counter()
         runner.forward(bufs)
         torch.cuda.synchronize()
@@ -182,9 +228,14 @@ def main():
         link[1] += d
         fwd_ms += (tb - ta) * 1e3
         bwd_ms += (tc - tb) * 1e3
+        steps_done += 1
+        elapsed = tc - t0
+        if elapsed + elapsed / steps_done > args.time_budget:  # the next pass would not fit
+            break
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t0
     B.fpdt_profile_enable(False)
+    steps_requested, args.steps = args.steps, steps_done
 
     prof = {}
     for name, kind in (("fwd_sweep", B.FPDT_PROF_FWD), ("bwd_dkdv", B.FPDT_PROF_DKDV),
@@ -206,13 +257,15 @@ def main():
     achieved = dom_flops / (prof[dom]["total_ms"] * 1e-3) / 1e12 if prof[dom]["total_ms"] > 0 else 0.0
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": HBM_TRAFFIC_PER_LAUNCH.get((cfg.name, dom)),
+                "traffic": hbm_traffic_per_launch(cfg.name, dom),
                 "avg_launch_ms": prof[dom]["total_ms"] / max(1, prof[dom]["launches"]),
                 "launches": prof[dom]["launches"]}
 
     out = {
         "metric": "chunked causal attn fwd+bwd TFLOPS",
-        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": warm_done,
+        "steps_requested": steps_requested, "warmup_requested": args.warmup,
+        "warmup_workload": "same kernels, chunk and residency on the first %d tokens" % warm_S,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "S": cfg.S, "chunk": cfg.chunk, "Hq": cfg.Hq, "Hkv": cfg.Hkv,
@@ -265,6 +318,8 @@ def main():
         src_k = Kdev if cfg.kv_on_host else bufs.K
         src_v = Vdev if cfg.kv_on_host else bufs.V
         out["cpu_baseline"] = cpu_baseline(torch, cfg, src_k, src_v, seed)
+    out["wall_s"] = time.perf_counter() - T_START
+    out["fits_in_driver_run"] = out["wall_s"] < 600.0
     print(json.dumps(out))
 
 
