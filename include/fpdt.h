@@ -127,6 +127,29 @@ int fpdt_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *L
                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * fpdt_attn_fwd for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as fpdt_attn_fwd
+ * (same kernels, so the same bits), except that the workspace is a device array built into the
+ * library, FPDT_NOALLOC_SCRATCH_BYTES per GPU, held from the library's load until the process
+ * ends.  The call makes no hipMalloc / hipFree, creates no stream or event and records no
+ * profiling events (fpdt_profile_enable does not see it).
+ *   - Tensors are resident: FPDT_KV_ON_HOST / FPDT_ACT_ON_HOST give FPDT_ERR_UNSUPPORTED.
+ *   - Sizes whose fpdt_attn_workspace_bytes(..., 0) exceeds FPDT_NOALLOC_SCRATCH_BYTES give
+ *     FPDT_ERR_WORKSPACE and enqueue nothing.  bf16 without FPDT_PAIRWISE needs
+ *     S / 32 * Hkv * (D / 16 + 2 * ceil(D / 32)) KiB: S * Hkv <= 65,536 at D = 128.
+ *   - Every call on a GPU uses that GPU's one array and finds the previous call's contents in
+ *     it.  Nothing has to start at zero (a call writes every byte it later reads), but two
+ *     calls that overlap in time on one GPU (different streams, or different threads) race on
+ *     it: keep such calls on one stream, or order them with events.
+ *   - The array's address is looked up on the first call on each device (hipGetSymbolAddress;
+ *     not a stream operation): make that first call outside stream capture.
+ */
+enum { FPDT_NOALLOC_SCRATCH_BYTES = 32 << 20 };
+int fpdt_attn_fwd_noalloc(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                          int64_t S, int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype,
+                          unsigned flags, void *stream);
+
+/*
  * Backward (Sec. 4.2, Fig. 7; operand set of Sec. 3.1).  Computes
  * Delta = rowsum(dO * O) once, then for every chunk pair (i >= j), in the chosen loop
  * order, recomputes p = exp(scale q k^T - LSE) (masked on diagonal pairs) and adds

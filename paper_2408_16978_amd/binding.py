@@ -21,6 +21,7 @@ FPDT_BWD_KV_OUTER = 1 << 2
 FPDT_BWD_Q_OUTER = 1 << 3
 FPDT_PAIRWISE = 1 << 4
 FPDT_CHUNK_MULTIPLE = 256
+FPDT_NOALLOC_SCRATCH_BYTES = 32 << 20
 FPDT_PROF_FWD, FPDT_PROF_DKDV, FPDT_PROF_DQ, FPDT_PROF_H2D, FPDT_PROF_D2H = range(5)
 FPDT_DEBUG_POISON_STAGING, FPDT_DEBUG_DELAY_COPIES = 1, 2
 
@@ -50,6 +51,8 @@ def load():
     L.fpdt_attn_pick_chunk.argtypes = [i64, ci, ci, ci, ci, cu, sz]
     L.fpdt_attn_fwd.restype = ci
     L.fpdt_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, ci, ci, ci, cf, ci, cu, vp, sz, vp]
+    L.fpdt_attn_fwd_noalloc.restype = ci
+    L.fpdt_attn_fwd_noalloc.argtypes = [vp, vp, vp, vp, vp, i64, i64, ci, ci, ci, cf, ci, cu, vp]
     L.fpdt_attn_bwd.restype = ci
     L.fpdt_attn_bwd.argtypes = [vp] * 9 + [i64, i64, ci, ci, ci, cf, ci, cu, vp, sz, vp]
     L.fpdt_attn_fwd_blocksparse.restype = ci
@@ -148,6 +151,15 @@ def fpdt_attn_fwd(Q, K, V, O, LSE, chunk, scale, flags=0, workspace=None, stream
     st = load().fpdt_attn_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), S, chunk, Hq, Hkv, D,
                               float(scale), _dtype_code(Q), flags, ws_ptr, ws_bytes,
                               _stream_handle(stream))
+    _check(st)
+
+
+def fpdt_attn_fwd_noalloc(Q, K, V, O, LSE, chunk, scale, flags=0, stream=None):
+    """fpdt_attn_fwd on the library's built-in scratch array: no workspace argument, no allocation."""
+    S, Hq, D = Q.shape
+    Hkv = K.shape[1]
+    st = load().fpdt_attn_fwd_noalloc(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), S, chunk, Hq, Hkv,
+                                      D, float(scale), _dtype_code(Q), flags, _stream_handle(stream))
     _check(st)
 
 

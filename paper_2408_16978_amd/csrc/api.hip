@@ -253,6 +253,31 @@ int get_ctx(DeviceCtx** out)
     return FPDT_OK;
 }
 
+// ---- workspace of the entry point that allocates nothing (fpdt_attn_fwd_noalloc) ----
+// A file-scope device array stands in for the caller's workspace.  Every GPU the library runs
+// on holds its own copy at its own address until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress: the device address is looked up once per
+// device, with that device current, and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[FPDT_NOALLOC_SCRATCH_BYTES];
+void* g_scratch_ptr[64] = {};
+thread_local bool g_no_alloc_call = false;  // set while fpdt_attn_fwd_noalloc runs: no event creation
+
+int scratch_for_current_device(void** out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return fail(FPDT_ERR_HIP, "device index %d out of range", dev);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || reinterpret_cast<uintptr_t>(ptr) % 256 != 0)
+            return fail(FPDT_ERR_HIP, "static scratch array has no usable device address");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return FPDT_OK;
+}
+
 // Event bookkeeping of one call.  The schedules wait for "buffer free" / "copied out" events
 // before they reuse a staging buffer; the first use of a buffer in a call has no such event yet
 // (every buffer is free when a call starts: the call's fork orders it behind the stream's
@@ -334,7 +359,7 @@ struct ProfScope {
     bool live = false;
     ProfScope(int kind, hipStream_t s) : st(s)
     {
-        if (!g_prof_on.load(std::memory_order_relaxed)) return;
+        if (!g_prof_on.load(std::memory_order_relaxed) || g_no_alloc_call) return;
         if (hipEventCreate(&r.a) != hipSuccess) return;
         if (hipEventCreate(&r.b) != hipSuccess) {
             (void)hipEventDestroy(r.a);
@@ -818,7 +843,7 @@ int64_t fpdt_attn_pick_chunk(int64_t S, int Hq, int Hkv, int D, int dtype, unsig
 static int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, float* LSE, int64_t S,
                          int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype, unsigned flags,
                          const unsigned char* chunk_mask, bool sparse, void* workspace,
-                         size_t workspace_bytes, void* stream)
+                         size_t workspace_bytes, void* stream, bool static_workspace = false)
 {
     g_err.clear();
     g_h2d_bytes = g_d2h_bytes = 0;
@@ -827,7 +852,10 @@ static int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, f
     TRY(validate_scalars(p, S, chunk, Hq, Hkv, D, scale, dtype, flags));
     if (sparse) TRY(take_mask(p, chunk_mask));
     const size_t need = plan_fwd(p, nullptr).total;
-    if (need && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256))
+    if (static_workspace) {
+        if (need > workspace_bytes)
+            return fail(FPDT_ERR_WORKSPACE, "these sizes need %zu bytes of workspace; the built-in scratch array of fpdt_attn_fwd_noalloc holds %zu (use fpdt_attn_fwd with a workspace of your own)", need, workspace_bytes);
+    } else if (need && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256))
         TRY(check_workspace(workspace, workspace_bytes, need));
     const size_t qbytes = (size_t)S * Hq * D * p.esize(), kbytes = (size_t)S * Hkv * D * p.esize();
     TRY(check_ptr(Q, qbytes, p.act_host(), "Q"));
@@ -835,7 +863,8 @@ static int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, f
     TRY(check_ptr(V, kbytes, p.kv_host(), "V"));
     TRY(check_ptr(O, qbytes, p.act_host(), "O"));
     TRY(check_ptr(LSE, (size_t)S * Hq * 4, p.act_host(), "LSE"));
-    TRY(check_workspace(workspace, workspace_bytes, need));
+    // (the static array is not in HIP's allocation table: its size and alignment are known)
+    if (!static_workspace) TRY(check_workspace(workspace, workspace_bytes, need));
     const FwdPlan f = plan_fwd(p, workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g_mu);
@@ -851,6 +880,23 @@ int fpdt_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* L
 {
     return attn_fwd_impl(Q, K, V, O, LSE, S, chunk, Hq, Hkv, D, scale, dtype, flags, nullptr, false,
                          workspace, workspace_bytes, stream);
+}
+
+int fpdt_attn_fwd_noalloc(const void* Q, const void* K, const void* V, void* O, float* LSE, int64_t S,
+                          int64_t chunk, int Hq, int Hkv, int D, float scale, int dtype, unsigned flags,
+                          void* stream)
+{
+    g_err.clear();
+    // the offload schedules create their side streams and events on first use
+    if (flags & (FPDT_KV_ON_HOST | FPDT_ACT_ON_HOST))
+        return fail(FPDT_ERR_UNSUPPORTED, "fpdt_attn_fwd_noalloc takes resident tensors only (no offload flags)");
+    void* ws = nullptr;
+    TRY(scratch_for_current_device(&ws));
+    g_no_alloc_call = true;
+    const int rc = attn_fwd_impl(Q, K, V, O, LSE, S, chunk, Hq, Hkv, D, scale, dtype, flags, nullptr, false,
+                                 ws, (size_t)FPDT_NOALLOC_SCRATCH_BYTES, stream, true);
+    g_no_alloc_call = false;
+    return rc;
 }
 
 int fpdt_attn_fwd_blocksparse(const void* Q, const void* K, const void* V, void* O, float* LSE,
