@@ -94,24 +94,22 @@ def test_bf16_odd_tile_counts_and_ungrouped_heads(S, chunk, Hq, Hkv, D):
 @pytest.mark.parametrize("Hq,Hkv,D", [(4, 4, 80), (8, 2, 128)])
 def test_bf16_score_distributions_beyond_gaussian(kind, Hq, Hkv, D):
     """Running maxima that rise in every tile, scores with a large common offset, and peaked
-    rows: O, LSE and dV, in the one-launch and in the pair-by-pair schedule.  dQ and dK are
-    only printed here: with peaked rows dS = p (dP - Delta) cancels almost completely, and the
-    bf16 rounding of the stored O inside Delta (an input of the backward, Sec. 3.1) then
-    dominates them whatever the kernel does."""
+    rows, in the one-launch and in the pair-by-pair schedule.  O, LSE and dV meet the plain bf16
+    budget.  With such scores dS = p (dP - Delta) cancels almost completely, and the roundings the
+    method itself prescribes (the stored bf16 O inside Delta, Sec. 3.1; dS rounded to bf16 for its
+    MFMAs) then weigh more in dQ and dK than the plain budget allows, whatever the kernel does:
+    their budget adds six standard deviations of that rounding noise (parity.backward_noise)."""
     S, chunk = 2048, 256
     announce("bf16", kind, S, chunk, Hq, Hkv, D)
     Q, K, V, dO = inputs.structured(kind, S, Hq, Hkv, D, "bf16", seed=6)
     scale = D ** -0.5
     ref = parity.oracle_full(Q, K, V, dO, scale)
+    sigma = parity.backward_noise(Q, K, V, dO, ref, scale)
     for flags in (0, B.FPDT_PAIRWISE | B.FPDT_BWD_KV_OUTER):
         out = run(Q, K, V, dO, chunk, scale, flags)
         print(parity.check_all(out, ref, True, names=("O", "LSE", "dV")))
         for n in ("dQ", "dK"):
-            got, r = parity.to64(out[n]), ref[n]
-            assert np.isfinite(got).all(), n
-            rms = np.sqrt((r ** 2).mean(axis=-1, keepdims=True))
-            rel = np.abs(got - r) / np.where(rms > 0, rms, np.inf)  # row 0 of dQ is exactly zero
-            print("  (information)", n, "worst |err| / row rms:", float(rel.max()))
+            parity.check_with_noise(n, out[n], ref[n], sigma[n], label=kind)
 
 
 @pytest.mark.parametrize("flags", [B.FPDT_KV_ON_HOST | B.FPDT_BWD_KV_OUTER,
@@ -158,6 +156,27 @@ def test_offload_event_ordering_with_poisoned_buffers_and_delayed_copies(flags):
         assert torch.equal(out[n].cpu(), base[n].cpu()), n
     with pytest.raises(B.FpdtError):
         B.fpdt_debug_configure(1 << 7)
+
+
+@pytest.mark.parametrize("S,Hq,Hkv,D,flags,forced", [(6144, 8, 2, 128, B.FPDT_KV_ON_HOST, 1536),
+                                                      (4096, 4, 4, 80, 0, None)])
+def test_picked_chunk_runs_to_parity(S, Hq, Hkv, D, flags, forced):
+    """fpdt_attn_pick_chunk (Sec. 5.3) returns a chunk the entry points accept, within the
+    workspace limit it was given, and forward + backward at that chunk match the oracle: once
+    with a limit that forces a small chunk of a sequence that is not a power of two (K/V
+    offloaded), once without a limit (the whole short sequence is one chunk)."""
+    BF = B.FPDT_DTYPE_BF16
+    limit = 0
+    if forced:
+        limit = max(B.fpdt_attn_workspace_bytes(S, forced, Hq, Hkv, D, BF, flags, b) for b in (False, True))
+    chunk = B.fpdt_attn_pick_chunk(S, Hq, Hkv, D, BF, flags, limit)
+    announce("picked chunk", S, Hq, Hkv, D, flags, limit, "->", chunk)
+    assert chunk == (forced or S)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=12)
+    scale = D ** -0.5
+    ref = parity.oracle_full(Q, K, V, dO, scale)
+    out = run(Q, K, V, dO, chunk, scale, flags)
+    print(parity.check_all(out, ref, True))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
