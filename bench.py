@@ -70,6 +70,10 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference for "
                          "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--calibrate-mfma", action="store_true",
+                    help="run only the library's MFMA calibration loops (what this GPU sustains on the "
+                         "kernels' MFMA instruction with random operands, alone, with the softmax's vector "
+                         "instructions in between, and with operands freshly read from LDS) and print them")
     return ap.parse_args()
 
 
@@ -128,6 +132,19 @@ def main():
     import torch
     from paper_2408_16978_amd import binding as B, inputs, runner
 
+    if args.calibrate_mfma:
+        torch.cuda.set_device(0)
+        cal = {}
+        for rep in range(2):  # the second pass is the one reported (clocks settled)
+            for kind, name in enumerate(B.FPDT_CAL_KINDS):
+                tf, ms = B.fpdt_calibrate_mfma(kind, 40000)
+                cal[name] = {"tflops": tf, "frac_of_peak": tf / PEAK_BF16_TFLOPS, "ms": ms}
+        print(json.dumps({"mfma_calibration": cal, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                          "note": "v_mfma_f32_32x32x16_bf16 on random operands of order one, one workgroup "
+                                  "per compute unit; reg = register operands, lds1 = one LDS fragment per "
+                                  "MFMA, lds2 = one per two MFMAs, softmax = 4 vector instructions per MFMA "
+                                  "(fma, exp2, add, cvt_pk / max3), 1w / 2w = waves per SIMD"}))
+        return
     cfg = inputs.CONFIGS[args.config]
     if args.chunk or args.seq or args.offload is not None:
         import dataclasses

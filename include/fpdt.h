@@ -77,9 +77,11 @@ enum {
     FPDT_BWD_Q_OUTER = 1u << 3,
     /* Run the chunk-pair schedule launch by launch (carried fp32 state between pairs)
      * even when every tensor is resident.  Without this bit and without offload flags
-     * the bf16 path walks the same chunk pairs inside one launch per kernel.  The
-     * offload pipeline always runs pair by pair, with the same kernels in the same
-     * order as this mode: the two agree bit for bit.  fp32 always runs pair by pair.  */
+     * the bf16 path ignores `chunk` (beyond validating it) and runs ONE causal sweep over
+     * the whole sequence per kernel: the same set of (query, key) tiles, no carried state
+     * between launches.  The offload pipeline always runs pair by pair, with the same
+     * kernels in the same order as this mode: the two agree bit for bit.  fp32 always
+     * runs pair by pair.                                                               */
     FPDT_PAIRWISE = 1u << 4
 };
 
@@ -88,24 +90,35 @@ enum {
  * needs for these arguments; 0 if the arguments are invalid or unsupported (call the
  * entry point itself for the status).  With FPDT_KV_ON_HOST the forward workspace
  * holds two key/value chunk buffers plus per-chunk state: it does not grow with S.
+ * The backward workspace under the offload flags is chunk-sized buffers (packed operands, raw
+ * and output staging, the accumulators of the side the outer loop holds fixed) PLUS state
+ * that grows with S, because the gradient of the side the inner loop walks is accumulated in
+ * fp32 on the device from one outer iteration to the next:
+ *   KV-outer (default with FPDT_KV_ON_HOST alone): dQ accumulator S * Hq * dpad(D) * 4 bytes
+ *       and Delta S * Hq * 4 (8 GiB + 64 MiB at S = 2M, Hq = 8, D = 128);
+ *   Q-outer: dK and dV accumulators 2 * S * Hkv * dpad(D) * 4 bytes (2 GiB at S = 2M,
+ *       Hkv = 2), plus Delta S * Hq * 4 unless FPDT_ACT_ON_HOST streams it per chunk;
+ * dpad(D) = D rounded up to a multiple of 32.
  */
 size_t fpdt_attn_workspace_bytes(int64_t S, int64_t chunk, int Hq, int Hkv, int D, int dtype,
                                  unsigned flags, int is_bwd);
 
 /*
- * Chunk size to use for a sequence of S tokens (Sec. 5.3: a chunk that is too small
- * starves the GPU, one that is too large wastes device memory on chunk buffers; the paper
- * settles on 64K tokens).  Returns the largest chunk c <= 131072 with S % c == 0, c a
+ * Chunk size to use for a sequence of S tokens (Sec. 5.3: a chunk that is too small starves
+ * the GPU, one that is too large wastes device memory on chunk buffers; the paper settles on
+ * 64K tokens).  Returns the largest chunk c <= FPDT_PREFERRED_CHUNK with S % c == 0, c a
  * multiple of FPDT_CHUNK_MULTIPLE (bf16 only), for which both workspaces
  * (fpdt_attn_workspace_bytes with is_bwd = 0 and 1) fit in max_workspace_bytes (0 = no
- * limit).  Larger is better up to that cap: one launch of the dK/dV kernel has
- * chunk / 256 * Hkv workgroups, which fills the 256 compute units only from 32K tokens on
- * at two KV heads, and every chunk pair costs a fixed launch, state load and state store
- * (measured on the Llama-8B head share at S = 256K with K/V offloaded: 457, 704, 897, 927,
- * 930 TFLOP/s at 8K, 16K, 32K, 64K, 128K tokens; at S = 2M: 933, 944, 946 at 32K, 64K, 128K).
+ * limit).  Why that cap: one launch of the dK/dV kernel has chunk / 256 * Hkv workgroups,
+ * which fills the 256 compute units only from 32K tokens on at two KV heads, and every
+ * chunk pair costs a fixed launch, state load and state store; measured on the Llama-8B head
+ * share with K/V offloaded the throughput rises steeply up to 32K tokens, by 3% (S = 256K)
+ * or 1% (S = 2M) from 32K to 64K, and by 0.3% at most from 64K to 128K, while every chunk-sized
+ * buffer doubles.  64K is the knee of that curve on this machine as well.
  * Returns 0 when the arguments are invalid or no chunk fits (fpdt_last_error says which).
  * Host logic only: no device is touched.
  */
+enum { FPDT_PREFERRED_CHUNK = 65536 };
 int64_t fpdt_attn_pick_chunk(int64_t S, int Hq, int Hkv, int D, int dtype, unsigned flags,
                              size_t max_workspace_bytes);
 
@@ -219,6 +232,35 @@ enum { FPDT_PROF_FWD = 0, FPDT_PROF_DKDV = 1, FPDT_PROF_DQ = 2, FPDT_PROF_H2D = 
        FPDT_PROF_D2H = 4, FPDT_PROF_KINDS = 5 };
 int fpdt_profile_enable(int on);
 int fpdt_profile_read(int kind, double *total_ms, int64_t *launches);
+
+/*
+ * Calibration of the roofline the attention kernels are measured against (Sec. 5.2 reports
+ * model FLOPs utilisation against the hardware's peak): what this GPU sustains on the MFMA
+ * instruction of the kernels (32x32x16 bf16, fp32 accumulation) with random operands of
+ * order one -- its clock under load depends on the data -- alone and in the company the
+ * attention kernels keep.  One workgroup per compute unit runs a fixed number of trips of a
+ * register / LDS loop; nothing on the attention path calls this.
+ *   kind  FPDT_CAL_MFMA_REG_2W / _1W      MFMAs on register operands, two / one wave per SIMD
+ *         FPDT_CAL_SOFTMAX_REG_2W / _1W   the same with the forward's softmax instructions
+ *                                         between the MFMAs: per MFMA one multiply-add, one
+ *                                         exp2, one add and a packed bf16 conversion or a
+ *                                         three-way maximum
+ *         FPDT_CAL_MFMA_LDS1_2W           the A operand of every MFMA freshly read from LDS
+ *                                         (1 KiB per MFMA: the forward and the dQ kernel)
+ *         FPDT_CAL_MFMA_LDS2_1W           one LDS fragment per two MFMAs, one wave per SIMD
+ *                                         (the dK/dV kernel)
+ *         FPDT_CAL_SOFTMAX_LDS1_2W, FPDT_CAL_SOFTMAX_LDS2_1W   both together
+ *   iters      trips of 24 MFMAs per wave (20000 runs about 0.1 s)
+ *   workspace  device memory, 256-byte aligned, >= FPDT_CAL_WORKSPACE_BYTES
+ *   tflops     out: executed MFMA TFLOP/s over the whole GPU;  ms: out (may be NULL)
+ * Synchronous: returns when the run has finished on `stream`.
+ */
+enum { FPDT_CAL_MFMA_REG_2W = 0, FPDT_CAL_MFMA_REG_1W = 1, FPDT_CAL_SOFTMAX_REG_2W = 2,
+       FPDT_CAL_SOFTMAX_REG_1W = 3, FPDT_CAL_MFMA_LDS1_2W = 4, FPDT_CAL_MFMA_LDS2_1W = 5,
+       FPDT_CAL_SOFTMAX_LDS1_2W = 6, FPDT_CAL_SOFTMAX_LDS2_1W = 7, FPDT_CAL_KINDS = 8 };
+enum { FPDT_CAL_WORKSPACE_BYTES = 1 << 20 };
+int fpdt_calibrate_mfma(int kind, int iters, void *workspace, size_t workspace_bytes,
+                        double *tflops, double *ms, void *stream);
 
 /*
  * Event-ordering checks for the offload pipeline (Sec. 4.2: copies on side streams, one buffer

@@ -22,6 +22,7 @@ FPDT_BWD_Q_OUTER = 1 << 3
 FPDT_PAIRWISE = 1 << 4
 FPDT_CHUNK_MULTIPLE = 256
 FPDT_NOALLOC_SCRATCH_BYTES = 32 << 20
+FPDT_PREFERRED_CHUNK = 65536
 FPDT_PROF_FWD, FPDT_PROF_DKDV, FPDT_PROF_DQ, FPDT_PROF_H2D, FPDT_PROF_D2H = range(5)
 FPDT_DEBUG_POISON_STAGING, FPDT_DEBUG_DELAY_COPIES = 1, 2
 
@@ -67,6 +68,9 @@ def load():
     L.fpdt_profile_enable.argtypes = [ci]
     L.fpdt_profile_read.restype = ci
     L.fpdt_profile_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    L.fpdt_calibrate_mfma.restype = ci
+    L.fpdt_calibrate_mfma.argtypes = [ci, ci, vp, sz, ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_double), vp]
     L.fpdt_debug_configure.restype = ci
     L.fpdt_debug_configure.argtypes = [cu]
     L.fpdt_last_error.restype = ctypes.c_char_p
@@ -130,6 +134,20 @@ def fpdt_profile_read(kind: int):
     ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
     _check(load().fpdt_profile_read(kind, ctypes.byref(ms), ctypes.byref(n)))
     return float(ms.value), int(n.value)
+
+
+FPDT_CAL_KINDS = ("mfma_reg_2w", "mfma_reg_1w", "softmax_reg_2w", "softmax_reg_1w", "mfma_lds1_2w",
+                  "mfma_lds2_1w", "softmax_lds1_2w", "softmax_lds2_1w")
+FPDT_CAL_WORKSPACE_BYTES = 1 << 20
+
+
+def fpdt_calibrate_mfma(kind: int, iters: int = 20000, stream=None):
+    """(TFLOP/s, milliseconds) of one calibration loop (see include/fpdt.h)."""
+    ws = torch.empty(FPDT_CAL_WORKSPACE_BYTES, dtype=torch.uint8, device="cuda")
+    tf, ms = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(load().fpdt_calibrate_mfma(kind, iters, ws.data_ptr(), ws.numel(), ctypes.byref(tf),
+                                      ctypes.byref(ms), _stream_handle(stream)))
+    return float(tf.value), float(ms.value)
 
 
 def fpdt_attn_workspace_bytes(S, chunk, Hq, Hkv, D, dtype, flags=0, is_bwd=False) -> int:

@@ -14,7 +14,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 SRC_DIR = os.path.join(PKG, "csrc")
 BUILD_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libfpdt.so")
-SOURCES = ["api.hip", "pack.hip", "fwd_bf16.hip", "bwd_bf16.hip", "f32_path.hip"]
+SOURCES = ["api.hip", "pack.hip", "fwd_bf16.hip", "bwd_bf16.hip", "f32_path.hip", "calibrate.hip"]
 # token-wise chunked neighbours (library GEMMs): a library of their own, linked against rocBLAS
 TW_LIB = os.path.join(PKG, "libfpdt_tokenwise.so")
 TW_SOURCES = ["tokenwise.hip"]
@@ -27,8 +27,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 
 def _compile(name: str) -> str:
     obj = os.path.join(BUILD_DIR, name.replace(".hip", ".o"))
-    extra = os.environ.get("FPDT_EXTRA_HIPCC_FLAGS", "").split()  # kernel experiments only
-    cmd = [HIPCC] + FLAGS + extra + ["-c", os.path.join(SRC_DIR, name), "-o", obj]
+    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(SRC_DIR, name), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s" % (name, r.stderr))

@@ -137,6 +137,12 @@ void launch_f32_bwd_pair(const F32BwdArgs& a, hipStream_t st);
 void launch_merge(const void* Oa, const float* La, const void* Ob, const float* Lb, void* Oo,
                   float* Lo, int64_t rows, int Hq, int D, int is_bf16, hipStream_t st);
 
+// Calibration loops (csrc/calibrate.hip): returns the waves per SIMD of the launched variant, 0 for
+// an unknown kind.  One launch executes blocks * (waves per SIMD * 4) * iters * 24 MFMAs.
+enum { CALIBRATE_MFMA_PER_TRIP = 24 };
+void launch_calibrate_fill(void* in, hipStream_t st);
+int launch_calibrate(int kind, float* out, const void* in, int iters, int blocks, hipStream_t st);
+
 // zero-fill by kernel (safe under graph capture)
 void launch_zero(void* p, size_t bytes, hipStream_t st);
 void launch_fill_bytes(void* p, size_t bytes, unsigned char byte, hipStream_t st);

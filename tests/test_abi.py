@@ -46,6 +46,8 @@ def test_header_constants_match_binding():
         m = re.search(name + r"\s*=\s*1u\s*<<\s*(\d+)", text)
         assert m and getattr(B, name) == 1 << int(m.group(1)), name
     assert re.search(r"FPDT_CHUNK_MULTIPLE\s*=\s*256", text) and B.FPDT_CHUNK_MULTIPLE == 256
+    assert re.search(r"FPDT_PREFERRED_CHUNK\s*=\s*65536", text) and B.FPDT_PREFERRED_CHUNK == 65536
+    assert re.search(r"FPDT_NOALLOC_SCRATCH_BYTES\s*=\s*32\s*<<\s*20", text) and B.FPDT_NOALLOC_SCRATCH_BYTES == 32 << 20
 
 
 def _fwd(lib, S=1024, chunk=256, Hq=2, Hkv=2, D=64, scale=0.125, dtype=B.FPDT_DTYPE_BF16, flags=0,
@@ -100,14 +102,29 @@ def test_workspace_sizes():
     c = ws(1 << 20, 65536, 8, 1, 128, bf, B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST, True)
     d = ws(1 << 21, 65536, 8, 1, 128, bf, B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST, True)
     assert d - c == 2 * (1 << 20) * 1 * 128 * 4
+    # backward with only K/V offloaded: the part that grows with S is the documented one,
+    #   KV-outer (default): fp32 dQ accumulator S * Hq * D * 4 and Delta S * Hq * 4
+    #   Q-outer:            fp32 dK and dV accumulators 2 * S * Hkv * D * 4 and Delta S * Hq * 4
+    kvh = B.FPDT_KV_ON_HOST
+    for S1, S2 in ((1 << 18, 1 << 21), (1 << 19, 1 << 20)):
+        grow = ws(S2, 65536, 8, 2, 128, bf, kvh, True) - ws(S1, 65536, 8, 2, 128, bf, kvh, True)
+        assert grow == (S2 - S1) * 8 * (128 + 1) * 4
+        assert grow == ws(S2, 65536, 8, 2, 128, bf, kvh | B.FPDT_BWD_KV_OUTER, True) - ws(S1, 65536, 8, 2, 128, bf, kvh | B.FPDT_BWD_KV_OUTER, True)
+        grow_q = ws(S2, 65536, 8, 2, 128, bf, kvh | B.FPDT_BWD_Q_OUTER, True) - ws(S1, 65536, 8, 2, 128, bf, kvh | B.FPDT_BWD_Q_OUTER, True)
+        assert grow_q == (S2 - S1) * (2 * 2 * 128 + 8) * 4
+    # at the headline workload: 8 GiB + 64 MiB of S-sized state under KV-outer, 2 GiB + 64 MiB under Q-outer
+    assert ws(1 << 21, 65536, 8, 2, 128, bf, kvh, True) - ws(1 << 21, 65536, 8, 2, 128, bf, kvh | B.FPDT_BWD_Q_OUTER, True) \
+        == (1 << 21) * 8 * 128 * 4 - 2 * (1 << 21) * 2 * 128 * 4 - (65536 * 8 * 128 * 4 - 2 * 65536 * 2 * 128 * 4)
 
 
 def test_pick_chunk_host_logic(lib):
     BF, F32 = B.FPDT_DTYPE_BF16, B.FPDT_DTYPE_F32
-    # largest divisor of S up to the 128K cap
-    assert B.fpdt_attn_pick_chunk(2097152, 8, 2, 128, BF, B.FPDT_KV_ON_HOST) == 131072
+    # largest divisor of S up to the 64K knee of the measured curve
+    assert B.FPDT_PREFERRED_CHUNK == 65536
+    assert B.fpdt_attn_pick_chunk(2097152, 8, 2, 128, BF, B.FPDT_KV_ON_HOST) == 65536
     assert B.fpdt_attn_pick_chunk(65536, 4, 4, 80, BF) == 65536
-    assert B.fpdt_attn_pick_chunk(768 * 256, 8, 2, 128, BF) == 98304      # 3 * 2^15: divisor, multiple of 256
+    assert B.fpdt_attn_pick_chunk(768 * 256, 8, 2, 128, BF) == 65536      # 3 * 2^16 tokens
+    assert B.fpdt_attn_pick_chunk(640 * 256, 8, 2, 128, BF) == 40960      # 5 * 2^15: divisor, multiple of 256
     assert B.fpdt_attn_pick_chunk(1024, 2, 2, 64, F32) == 1024
     # the answer is always a legal chunk for the entry points and respects the workspace limit
     for S, flags in ((2097152, B.FPDT_KV_ON_HOST), (1048576, B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST), (262144, 0)):
