@@ -60,6 +60,8 @@ def parse():
     ap.add_argument("--keep", type=float, default=None,
                     help="block-sparse attention (Sec. 5.5): keep each below-diagonal chunk pair "
                          "with this probability (seeded), always keep the diagonal")
+    ap.add_argument("--bwd-order", choices=["kv", "q"], default=None,
+                    help="backward chunk-pair loop order (Sec. 4.2); default: the library's choice")
     ap.add_argument("--time-budget", type=float, default=TIMED_BUDGET_S,
                     help="seconds of timed passes: fewer than --steps are timed if they do not fit "
                          "(never fewer than one)")
@@ -164,6 +166,9 @@ def main():
     seed = 2024
     Q, K, V, dO = inputs.make_qkvdo(cfg.S, cfg.Hq, cfg.Hkv, cfg.D, cfg.dtype, seed, device="cuda")
     flags = (B.FPDT_KV_ON_HOST if cfg.kv_on_host else 0) | (B.FPDT_ACT_ON_HOST if cfg.act_on_host else 0)
+    if args.bwd_order is not None:
+        flags |= B.FPDT_BWD_Q_OUTER if args.bwd_order == "q" else B.FPDT_BWD_KV_OUTER
+        cfg = __import__("dataclasses").replace(cfg, name="%s[bwd=%s-outer]" % (cfg.name, args.bwd_order))
     mask = None
     pair_frac = 1.0  # kept share of the dense causal FLOPs
     if args.keep is not None:

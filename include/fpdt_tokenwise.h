@@ -7,9 +7,9 @@
  *
  *   fpdt_tw_loss_fwd_bwd   softmax cross-entropy over the vocabulary with its last linear
  *                          projection, forward and backward fused per chunk: the fp32 logits
- *                          [rows, vocab] never exist for more than one chunk (the paper's
- *                          "memory spike ... in the final calculation of softmax and
- *                          cross-entropy loss"; suggested chunk count: vocab / hidden * 2).
+ *                          [rows, vocab] never exist for more than one chunk (Sec. 5.4 names
+ *                          the loss over a large vocabulary as the place where memory peaks
+ *                          and suggests vocab / hidden * 2 chunks).
  *   fpdt_tw_linear_*       the per-chunk QKV projection in front of the attention.
  *   fpdt_tw_ffn_*          the feed-forward block, chunked with twice the attention's chunk
  *                          count, forward and (recomputing) backward.
