@@ -62,6 +62,10 @@ def parse():
                          "with this probability (seeded), always keep the diagonal")
     ap.add_argument("--bwd-order", choices=["kv", "q"], default=None,
                     help="backward chunk-pair loop order (Sec. 4.2); default: the library's choice")
+    ap.add_argument("--bwd", choices=["stored-ds", "recompute"], default=None,
+                    help="backward form (default: the workload's): stored-ds = FPDT_BWD_STORE_DS, dQ from "
+                         "the dS tiles the dK/dV kernel writes (5 executed GEMMs per chunk pair, chunk^2 * Hq "
+                         "* 2 bytes of workspace); recompute = dQ recomputes S and dP (7 GEMMs)")
     ap.add_argument("--time-budget", type=float, default=TIMED_BUDGET_S,
                     help="seconds of timed passes: fewer than --steps are timed if they do not fit "
                          "(never fewer than one)")
@@ -166,6 +170,11 @@ def main():
     seed = 2024
     Q, K, V, dO = inputs.make_qkvdo(cfg.S, cfg.Hq, cfg.Hkv, cfg.D, cfg.dtype, seed, device="cuda")
     flags = (B.FPDT_KV_ON_HOST if cfg.kv_on_host else 0) | (B.FPDT_ACT_ON_HOST if cfg.act_on_host else 0)
+    store_ds = cfg.store_ds if args.bwd is None else args.bwd == "stored-ds"
+    if store_ds != cfg.store_ds:
+        cfg = __import__("dataclasses").replace(cfg, store_ds=store_ds, name="%s[bwd=%s]" % (cfg.name, args.bwd))
+    if store_ds:
+        flags |= B.FPDT_BWD_STORE_DS
     if args.bwd_order is not None:
         flags |= B.FPDT_BWD_Q_OUTER if args.bwd_order == "q" else B.FPDT_BWD_KV_OUTER
         cfg = __import__("dataclasses").replace(cfg, name="%s[bwd=%s-outer]" % (cfg.name, args.bwd_order))
@@ -206,7 +215,7 @@ def main():
     else:
         nc = warm_S // cfg.chunk
         dt = B.FPDT_DTYPE_BF16 if cfg.dtype == "bf16" else B.FPDT_DTYPE_F32
-        fwd_flags = bufs.flags & ~(B.FPDT_BWD_KV_OUTER | B.FPDT_BWD_Q_OUTER)
+        fwd_flags = bufs.flags & ~(B.FPDT_BWD_KV_OUTER | B.FPDT_BWD_Q_OUTER | B.FPDT_BWD_STORE_DS)
         wbufs = runner.Buffers(
             Q=bufs.Q[:warm_S], K=bufs.K[:warm_S], V=bufs.V[:warm_S], dO=bufs.dO[:warm_S],
             O=bufs.O[:warm_S], dQ=bufs.dQ[:warm_S], dK=bufs.dK[:warm_S], dV=bufs.dV[:warm_S],
@@ -271,8 +280,8 @@ def main():
     fwd_flops = cfg.flops_fwd() * pair_frac
 
     # dominant kernel: the one with the largest summed duration.  Algorithmic FLOPs of a
-    # kernel = 2*D*Hq*S(S+1)/2 per GEMM it is defined by (forward 2, dK/dV 4, dQ 3).
-    gemms = {"fwd_sweep": 2, "bwd_dkdv": 4, "bwd_dq": 3}
+    # kernel = 2*D*Hq*S(S+1)/2 per GEMM it is defined by (forward 2, dK/dV 4, dQ 3, or 1 from stored dS).
+    gemms = {"fwd_sweep": 2, "bwd_dkdv": 4, "bwd_dq": 1 if store_ds else 3}
     dom = max(gemms, key=lambda k: prof[k]["total_ms"])
     per_gemm = 2.0 * cfg.D * cfg.Hq * cfg.S * (cfg.S + 1) / 2.0 * pair_frac
     dom_flops = gemms[dom] * per_gemm * args.steps
@@ -291,7 +300,9 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "S": cfg.S, "chunk": cfg.chunk, "Hq": cfg.Hq, "Hkv": cfg.Hkv,
-                   "D": cfg.D, "kv_on_host": cfg.kv_on_host, "act_on_host": cfg.act_on_host},
+                   "D": cfg.D, "kv_on_host": cfg.kv_on_host, "act_on_host": cfg.act_on_host,
+                   "bwd": "stored-dS (5 executed GEMMs per chunk pair)" if store_ds else
+                          "recompute (7 executed GEMMs per chunk pair)"},
         "frac_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "fwd_ms": fwd_ms / args.steps, "bwd_ms": bwd_ms / args.steps,
         "fwd_tflops": fwd_flops / (fwd_ms / args.steps * 1e-3) / 1e12,
@@ -314,13 +325,15 @@ def main():
                                                           "h2d_1GiB": h1g, "d2h_1GiB": d1g}
     if args.resident_compare and cfg.kv_on_host and not cfg.act_on_host:
         # same kernels, same pair order, K/V resident: the difference is the exposed copy time
+        res_flags = B.FPDT_PAIRWISE | (flags & (B.FPDT_BWD_STORE_DS | B.FPDT_BWD_KV_OUTER | B.FPDT_BWD_Q_OUTER))
+        del bufs.ws_bwd  # the resident run brings a backward workspace of its own
         b2 = runner.Buffers(Q=bufs.Q, K=Kdev, V=Vdev, dO=bufs.dO, O=bufs.O, LSE=bufs.LSE, dQ=bufs.dQ,
                             dK=torch.empty_like(Kdev), dV=torch.empty_like(Vdev),
                             ws_fwd=B.alloc_workspace(cfg.S, cfg.chunk, cfg.Hq, cfg.Hkv, cfg.D,
                                                      B.FPDT_DTYPE_BF16, B.FPDT_PAIRWISE, False),
                             ws_bwd=B.alloc_workspace(cfg.S, cfg.chunk, cfg.Hq, cfg.Hkv, cfg.D,
-                                                     B.FPDT_DTYPE_BF16, B.FPDT_PAIRWISE, True),
-                            chunk=cfg.chunk, scale=cfg.scale, flags=B.FPDT_PAIRWISE, chunk_mask=mask)
+                                                     B.FPDT_DTYPE_BF16, res_flags, True),
+                            chunk=cfg.chunk, scale=cfg.scale, flags=res_flags, chunk_mask=mask)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         runner.forward(b2)

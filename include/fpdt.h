@@ -82,7 +82,18 @@ enum {
      * between launches.  The offload pipeline always runs pair by pair, with the same
      * kernels in the same order as this mode: the two agree bit for bit.  fp32 always
      * runs pair by pair.                                                               */
-    FPDT_PAIRWISE = 1u << 4
+    FPDT_PAIRWISE = 1u << 4,
+    /* Backward only (bf16; the forward ignores it): the stored-dS backward.  The paper's
+     * backward, like any FlashAttention backward, recomputes the probabilities per chunk
+     * pair (Sec. 3.1, 4.2); the two-kernel form used here (no atomics) recomputes the
+     * scores and dP twice, once for dK/dV and once for dQ: 7 GEMMs per pair for the
+     * algorithmic 5.  With this flag the dK/dV kernel also writes the rounded dS tiles of
+     * the pair (the very bf16 values its own MFMAs consume) to the workspace, and dQ is
+     * one GEMM over them: 5 executed GEMMs, the same dQ numerics (dS was already rounded
+     * to bf16 for its MFMA), for chunk * chunk * Hq * 2 bytes of workspace (64 GiB at
+     * chunk = 65,536 and Hq = 8: sized for a 288 GB GPU) and that many bytes of HBM traffic
+     * each way per pair.  Implies the pair-by-pair schedule (as FPDT_PAIRWISE).           */
+    FPDT_BWD_STORE_DS = 1u << 5
 };
 
 /*

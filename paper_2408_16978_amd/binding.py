@@ -20,6 +20,7 @@ FPDT_ACT_ON_HOST = 1 << 1
 FPDT_BWD_KV_OUTER = 1 << 2
 FPDT_BWD_Q_OUTER = 1 << 3
 FPDT_PAIRWISE = 1 << 4
+FPDT_BWD_STORE_DS = 1 << 5
 FPDT_CHUNK_MULTIPLE = 256
 FPDT_NOALLOC_SCRATCH_BYTES = 32 << 20
 FPDT_PREFERRED_CHUNK = 65536

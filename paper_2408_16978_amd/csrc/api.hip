@@ -42,8 +42,8 @@ int fail(int code, const char* fmt, ...)
                         __FILE__, __LINE__);                                                  \
     } while (0)
 
-constexpr unsigned KNOWN_FLAGS =
-    FPDT_KV_ON_HOST | FPDT_ACT_ON_HOST | FPDT_BWD_KV_OUTER | FPDT_BWD_Q_OUTER | FPDT_PAIRWISE;
+constexpr unsigned KNOWN_FLAGS = FPDT_KV_ON_HOST | FPDT_ACT_ON_HOST | FPDT_BWD_KV_OUTER | FPDT_BWD_Q_OUTER |
+                               FPDT_PAIRWISE | FPDT_BWD_STORE_DS;
 
 struct Problem {
     int64_t S, C, u;
@@ -54,7 +54,8 @@ struct Problem {
     size_t esize() const { return bf16() ? 2 : 4; }
     bool kv_host() const { return flags & FPDT_KV_ON_HOST; }
     bool act_host() const { return flags & FPDT_ACT_ON_HOST; }
-    bool fused() const { return bf16() && !(flags & (FPDT_KV_ON_HOST | FPDT_ACT_ON_HOST | FPDT_PAIRWISE)); }
+    bool store_ds() const { return flags & FPDT_BWD_STORE_DS; }
+    bool fused() const { return bf16() && !(flags & (FPDT_KV_ON_HOST | FPDT_ACT_ON_HOST | FPDT_PAIRWISE | FPDT_BWD_STORE_DS)); }
     bool q_outer() const
     {
         if (flags & FPDT_BWD_Q_OUTER) return true;
@@ -96,6 +97,9 @@ int validate_scalars(Problem& p, int64_t S, int64_t chunk, int Hq, int Hkv, int 
     if (D != 64 && D != 80 && D != 128) return fail(FPDT_ERR_UNSUPPORTED, "head dim %d not in {64, 80, 128}", D);
     if (dtype == FPDT_DTYPE_BF16 && chunk % FPDT_CHUNK_MULTIPLE != 0) return fail(FPDT_ERR_UNSUPPORTED, "bf16 chunk=%lld is not a multiple of %d", (long long)chunk, (int)FPDT_CHUNK_MULTIPLE);
     if (dtype == FPDT_DTYPE_F32 && (flags & (FPDT_KV_ON_HOST | FPDT_ACT_ON_HOST))) return fail(FPDT_ERR_UNSUPPORTED, "fp32 path has no host offload");
+    if (dtype == FPDT_DTYPE_F32 && (flags & FPDT_BWD_STORE_DS)) return fail(FPDT_ERR_UNSUPPORTED, "fp32 path has no stored-dS backward");
+    if ((flags & FPDT_BWD_STORE_DS) && (double)chunk * (double)chunk * Hq / 1024.0 >= 2147483648.0)
+        return fail(FPDT_ERR_UNSUPPORTED, "stored-dS backward: chunk=%lld with %d heads has too many dS tiles (chunk^2 * Hq must stay below 2^41)", (long long)chunk, Hq);
     if ((flags & FPDT_ACT_ON_HOST) && (flags & FPDT_BWD_KV_OUTER)) return fail(FPDT_ERR_UNSUPPORTED, "FPDT_ACT_ON_HOST needs the Q-outer backward order");
     if (S > (int64_t)1 << 30 || (int64_t)Hq * (S / 32 + 1) > (int64_t)1 << 30) return fail(FPDT_ERR_UNSUPPORTED, "S=%lld beyond launch limits", (long long)S);
     p.S = S; p.C = chunk; p.u = S / chunk; p.Hq = Hq; p.Hkv = Hkv; p.D = D; p.dtype = dtype;
@@ -167,6 +171,8 @@ struct BwdPlan {
     char* act_raw[2] = {nullptr, nullptr};  // [Q | dO | O] chunk
     float* lse_buf[2] = {nullptr, nullptr};
     char* dq_out[2] = {nullptr, nullptr};
+    void* ds_frag = nullptr;  // stored-dS backward: the dS tiles of one chunk pair
+    float* stat2 = nullptr;   // row statistics of the packed query rows, as the dK/dV kernel reads them
     size_t total = 0;
 };
 
@@ -185,6 +191,7 @@ BwdPlan plan_bwd(const Problem& p, void* ws)
         f.Knat = b.take((size_t)(rows / 32) * p.Hkv * nat_block_bytes(p.D));
         f.Vnat = b.take((size_t)(rows / 32) * p.Hkv * nat_block_bytes(p.D));
         if (!p.act_host()) f.Delta = b.take<float>((size_t)p.Hq * p.S * 4);
+        f.stat2 = b.take<float>((size_t)(rows / 32) * p.Hq * 64 * 4);
         if (!p.fused()) {
             // accumulators: the side that the outer loop holds fixed needs one chunk, the
             // other side one slot per chunk of the sequence
@@ -192,6 +199,7 @@ BwdPlan plan_bwd(const Problem& p, void* ws)
             f.acc_dq = b.take<float>(bwd_acc_dq_bytes(qo ? p.C : p.S, p.Hq, p.D));
             f.acc_dk = b.take<float>(bwd_acc_dkv_bytes(qo ? p.S : p.C, p.Hkv, p.D));
             f.acc_dv = b.take<float>(bwd_acc_dkv_bytes(qo ? p.S : p.C, p.Hkv, p.D));
+            if (p.store_ds()) f.ds_frag = b.take(bwd_ds_bytes(p.C, p.C, p.Hq));
             if (p.kv_host())
                 for (int i = 0; i < 2; ++i) {
                     f.kv_raw[i] = b.take<char>(2 * p.kv_chunk_bytes());
@@ -608,6 +616,7 @@ int bwd_bf16_fused(const Problem& p, const void* Q, const void* K, const void* V
 {
     launch_delta(O, dO, p.S, p.Hq, p.D, 1, f.Delta, p.S, st);
     launch_delta_head(Q, dO, K, V, LSE, p.S, DELTA_HEAD_ROWS, p.Hq, p.Hkv, p.D, p.scale, f.Delta, st);
+    launch_stat_pack(LSE, f.Delta, p.S, p.S, p.Hq, p.S / 32, f.stat2, st);
     launch_pack(Q, p.S, p.Hq, p.D, f.Qnat, nullptr, p.S / 32, st);
     launch_pack(dO, p.S, p.Hq, p.D, f.dOnat, nullptr, p.S / 32, st);
     launch_pack(K, p.S, p.Hkv, p.D, f.Knat, nullptr, p.S / 32, st);
@@ -617,6 +626,7 @@ int bwd_bf16_fused(const Problem& p, const void* Q, const void* K, const void* V
     a.Qnat = f.Qnat; a.dOnat = f.dOnat; a.q_head_stride_blocks = p.S / 32;
     a.Knat = f.Knat; a.Vnat = f.Vnat; a.kv_head_stride_blocks = p.S / 32;
     a.LSE = LSE; a.Delta = f.Delta; a.row_stat_stride = p.S;
+    a.stat2 = f.stat2;
     a.q_pos0 = 0; a.k_pos0 = 0; a.n_q = p.S; a.n_k = p.S;
     a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
     a.acc_dq = nullptr; a.acc_dk = nullptr; a.acc_dv = nullptr;
@@ -697,6 +707,7 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
     const char *Qi = nullptr, *dOi = nullptr, *Kj = nullptr, *Vj = nullptr;
     const float *LSEi = nullptr, *Deltai = nullptr;
     int64_t stat_stride = p.S;
+    bool stat_stale = true;  // f.stat2 does not hold the current query chunk's statistics yet
     for (size_t t = 0; t < pairs.size(); ++t) {
         const int64_t i = pairs[t].first, j = pairs[t].second;
         // both orders visit the key chunks of a query chunk, and the query chunks of a key chunk,
@@ -748,6 +759,7 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
             launch_pack(Qi, p.C, p.Hq, p.D, f.Qnat, nullptr, p.C / 32, st);
             launch_pack(dOi, p.C, p.Hq, p.D, f.dOnat, nullptr, p.C / 32, st);
             cur_i = i;
+            stat_stale = true;
         }
         // Rows that see only a few keys get their cancellation-safe Delta: the head of the
         // sequence (pair (0, 0)) and, with a chunk mask, the head of every query chunk that keeps
@@ -755,12 +767,17 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
         if (i == j && p.first_key_chunk(i) == i)
             launch_delta_head(Qi, dOi, Kj, Vj, LSEi, stat_stride, DELTA_HEAD_ROWS, p.Hq, p.Hkv, p.D,
                               p.scale, const_cast<float*>(Deltai), st);
+        if (stat_stale) {  // after the head rows have their final Delta
+            launch_stat_pack(LSEi, Deltai, stat_stride, p.C, p.Hq, p.C / 32, f.stat2, st);
+            stat_stale = false;
+        }
         // ---- the pair ----
         BwdArgs a;
         a.Q = Qi; a.dO = dOi; a.K = Kj; a.V = Vj;
         a.Qnat = f.Qnat; a.dOnat = f.dOnat; a.q_head_stride_blocks = p.C / 32;
         a.Knat = f.Knat; a.Vnat = f.Vnat; a.kv_head_stride_blocks = p.C / 32;
         a.LSE = LSEi; a.Delta = Deltai; a.row_stat_stride = stat_stride;
+        a.stat2 = f.stat2;
         a.q_pos0 = i * p.C; a.k_pos0 = j * p.C; a.n_q = p.C; a.n_k = p.C;
         a.Hq = p.Hq; a.Hkv = p.Hkv; a.D = p.D; a.scale = p.scale;
         a.acc_dq = f.acc_dq + (qo ? 0 : (size_t)i * acc_q_chunk);
@@ -770,6 +787,7 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
         a.dK = kvh ? f.dkv_out[ob_kv] : dK + (size_t)j * kvb;
         a.dV = kvh ? f.dkv_out[ob_kv] + kvb : dV + (size_t)j * kvb;
         a.dQ = acth ? f.dq_out[ob_q] : dQ + (size_t)i * qb;
+        a.dS_frag = f.ds_frag;  // null unless FPDT_BWD_STORE_DS: the dK/dV launch then writes the pair's dS tiles
 
         a.flags = (first_for_kv ? 0 : ACC_LOAD) | (last_for_kv ? ACC_FINAL : 0);
         if (kvh && last_for_kv) TRY(ev.wait(st, EV_DKV_COPIED0 + ob_kv));
@@ -784,7 +802,11 @@ int bwd_bf16_pairs(const Problem& p, const char* Q, const char* K, const char* V
 
         a.flags = (first_for_q ? 0 : ACC_LOAD) | (last_for_q ? ACC_FINAL : 0);
         if (acth && last_for_q) TRY(ev.wait(st, EV_OUT_COPIED0 + ob_q));
-        { PROF(FPDT_PROF_DQ, st); launch_bwd_dq(a, st); }
+        {
+            PROF(FPDT_PROF_DQ, st);
+            if (a.dS_frag) launch_bwd_dq_from_ds(a, st);  // one GEMM on the tiles just written
+            else launch_bwd_dq(a, st);
+        }
         if (acth && last_for_q) {
             TRY(ev.record(EV_OUT_DONE0 + ob_q, st));
             TRY(ev.wait(c->d2h, EV_OUT_DONE0 + ob_q));
@@ -812,6 +834,7 @@ size_t fpdt_attn_workspace_bytes(int64_t S, int64_t chunk, int Hq, int Hkv, int 
                                  unsigned flags, int is_bwd)
 {
     Problem p;
+    if (!is_bwd) flags &= ~(unsigned)FPDT_BWD_STORE_DS;  // backward-only flag
     if (validate_scalars(p, S, chunk, Hq, Hkv, D, 1.f, dtype, flags) != FPDT_OK) return 0;
     return is_bwd ? plan_bwd(p, nullptr).total : plan_fwd(p, nullptr).total;
 }
@@ -851,6 +874,7 @@ static int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, f
     g_err.clear();
     g_h2d_bytes = g_d2h_bytes = 0;
     if (!Q || !K || !V || !O || !LSE) return fail(FPDT_ERR_INVALID_ARG, "NULL tensor pointer");
+    flags &= ~(unsigned)FPDT_BWD_STORE_DS;  // backward-only flag
     Problem p;
     TRY(validate_scalars(p, S, chunk, Hq, Hkv, D, scale, dtype, flags));
     if (sparse) TRY(take_mask(p, chunk_mask));

@@ -38,12 +38,14 @@ struct BwdKernelArgs {
     const u32x4* Knat; const u32x4* Vnat;
     int64_t kv_head_stride_blocks;
     const float* LSE; const float* Delta; int64_t row_stat_stride;
+    const float* stat2;  // dK/dV kernel: per (head, 32-row block) 32 x LSE * log2(e), then 32 x -Delta
     int64_t q_pos0, k_pos0;
     int n_q, n_k;
     int Hq, Hkv, g, flags;
     float scale, c;
     float* acc_dq; float* acc_dk; float* acc_dv;
     uint16_t* dQ; uint16_t* dK; uint16_t* dV;
+    u32x4* dS;  // dS fragments of the launch (stored-dS backward), or null
 };
 
 // Store a transposed accumulator tile set (lane = one row, registers = channels) as bf16
@@ -92,7 +94,11 @@ __device__ __forceinline__ void store_rows_bf16(const floatx16 (&acc)[DB], float
 #define FPDT_MFMA_TO_VALU_NOPS() asm volatile("s_nop 7\n\ts_nop 4" ::: "memory")
 #define FPDT_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-template <int D>
+// STORE_DS: the rounded dS tiles, which are this kernel's own MFMA operands, are also written to
+// p.dS as 1 KiB fragments [head][32-query block][32-key block][s2][lane][8]: lane (key c, h') of
+// fragment s2 holds dS[q = 16 s2 + 8 (e / 4) + 4 h' + e % 4][key c], e = 0..7 -- exactly the register
+// contents.  bwd_dq_ds_kernel reads them back instead of recomputing S and dP.
+template <int D, bool STORE_DS>
 __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
 {
     constexpr int NW = 4, NK = 2;
@@ -177,7 +183,6 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     if (dend > n_qb_all) dend = n_qb_all;
     const int n_hot_iter = (n_qb_all - (int)dend) * p.g;  // walked first (descending order)
 
-    float pre_stat = 0.f;
     // Operand layout.  A step needs the 32 x D Q and dO blocks twice: as A operands contracted
     // over d (S = Q K^T, dP = dO V^T; lane = query row, 8 consecutive d) and contracted over the
     // query (dV^T += dO^T P, dK^T += Q^T dS; lane = d, 8 queries).  LDS holds each block ONCE, in
@@ -199,6 +204,9 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     // requests the row statistics), issue_one() sends one copy; a step calls it between its first
     // MFMA groups.
     uint64_t cp_src[2] = {0, 0};  // scalar registers: this wave's first fragment of each operand
+    uint64_t stat_src = 0;
+    uint64_t ds_next = 0;  // (STORE_DS) where the step that issue_begin() was last called for stores its dS fragments
+    const unsigned stat_addr[2] = {lds_address(stat0), lds_address(stat1)};
     // (DT even: the parity of every fragment a wave copies is the wave's; DT odd: chosen per copy)
     const int cp_lane_par[2] = {16 * (32 * half + (col ^ (4 * half))), 16 * (32 * half + (col ^ (4 * half) ^ 8))};
     const int cp_lane_off = cp_lane_par[wu & 1];
@@ -223,13 +231,21 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
         const int w64 = DT == 8 ? wu * 64 : 0;  // D = 128: the wave's first fragment of each operand
         cp_src[0] = uniform((uint64_t)(uintptr_t)(p.Qnat + blk * NAT_U4 + w64));
         cp_src[1] = uniform((uint64_t)(uintptr_t)(p.dOnat + blk * NAT_U4 + w64));
-        // raw value only: any arithmetic on it here would make the step wait for this load and,
-        // the counters being in order, for every operand copy issued before it
-        if (tid < 64) pre_stat = (tid < 32 ? p.LSE : p.Delta - 32)[(size_t)head * p.row_stat_stride + qb * 32 + tid];
+        // the block's row statistics (256 bytes, already in the form the step consumes) travel
+        // through the copy engine like the operands: no vector register, no wait of the compiler's
+        stat_src = uniform((uint64_t)(uintptr_t)(p.stat2 + blk * 64));
+        if constexpr (STORE_DS) {
+            // fragment pair index of (head, query block, this wave's first key block) in 32 bits (the
+            // API layer keeps a launch below 2^31 of them); computed here, beside the other scalar
+            // address work of the step's head, so that nothing but the stores sits among the MFMAs
+            const unsigned pair = uniform(((unsigned)head * (unsigned)n_qb_all + (unsigned)qb) * (unsigned)(p.n_k / 32) + (unsigned)(kw0 / 32));
+            ds_next = (uint64_t)(uintptr_t)p.dS + ((uint64_t)pair << 11);
+        }
     };
     // k = 0..3 (compile-time after unrolling): fragment 4 k + w of the step, i.e. fragment
     // 4 (k % 2) + w of operand k / 2; into_slot1 is a compile-time constant at every call
     auto issue_one = [&](int k, bool into_slot1) {
+        if (k == 0 && wu == 0) dwords_to_lds_at(stat_src, stat_addr[into_slot1], lane * 4);
         if constexpr (DT == 8) {
             frag_to_lds_at(cp_src[k / 2] + 1024u * (unsigned)(NW * (k % 2)), slot_lds[into_slot1] + 1024u * (unsigned)(NW * k), cp_lane_off);
         } else {
@@ -256,6 +272,8 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
     typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
     auto step = [&](auto masked_tag, int it, const u32x4* sl, const float* st, u32x4* nslot, float* nst) {
         constexpr bool MASKED = decltype(masked_tag)::value;
+        (void)nst;  // filled by the copy that issue_one(0, ..) sends with the next step's operands
+        const uint64_t ds_dst = ds_next;  // set when this step's operands were requested
         const bool more = it + 1 < n_iter;
         // the last step copies its own operands once more into the idle slot: the copies in the
         // MFMA sequence below then need no branch around them
@@ -390,6 +408,16 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
             df[1][1] = pack_half<1>(dp1);
             FPDT_SCHED_FENCE();
             // ---- D: dK^T += Q^T dS ----
+            if constexpr (STORE_DS && !MASKED) {
+                // In the unmasked steps (all but a few per launch) the next step's operand copies are
+                // waited for HERE, in front of this step's dS stores, not at the end of the step:
+                // vector-memory stores and loads complete out of order with each other, so a wait that
+                // has to cover the copies would cover the stores as well, and those have been in
+                // flight for a quarter of a step only.  Issued now, the stores have a whole step to
+                // drain.  (Compile-time choice: a run-time condition around the closing wait makes the
+                // register allocator spill the accumulators.)
+                wait_vmem_at_most<0>();
+            }
 #pragma unroll
             for (int i = 0; i < 2 * DB; ++i) {
                 const int u = 2 * DT + 2 * DB + i;
@@ -397,19 +425,30 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                 FPDT_MFMA_A(dk[0][db], fr[u % 6], df[0][s2]);
                 FPDT_MFMA_A(dk[1][db], fr[u % 6], df[1][s2]);
                 if (u + 4 < UFRAG) fr[(u + 4) % 6] = FPDT_AFRAG(u + 4);
+                if constexpr (STORE_DS) {
+                    // four 1 KiB stores spread over the MFMA pairs of this phase (issued behind the
+                    // step's last MFMA instead, in the shadow of the barrier: 265 against 260 ms):
+                    // fragment (kb, s2) of this step at [.. + kb][s2]; non-temporal, they are read
+                    // back once by another kernel
+                    constexpr int EVERY = 2 * DB >= 8 ? 2 : 1;
+                    if (i % EVERY == 0 && i / EVERY < 4) {
+                        const int f = i / EVERY;
+                        asm volatile("global_store_dwordx4 %0, %1, %2 nt"
+                                     :
+                                     : "v"(lane * 16), "v"(__builtin_bit_cast(u32x4, df[f / 2][f % 2])),
+                                       "s"(ds_dst + 1024u * (unsigned)f)
+                                     : "memory");
+                    }
+                }
                 FPDT_SCHED_FENCE();
             }
 #undef FPDT_AFRAG
         }
-        if (more && tid < 64) nst[tid] = tid < 32 ? pre_stat * LOG2E : -pre_stat;
-        wait_vmem_at_most<0>();  // the direct-to-LDS loads of step it+1 have landed
+        if constexpr (!STORE_DS || MASKED) wait_vmem_at_most<0>();  // the direct-to-LDS loads of step it+1 have landed
         barrier_no_fence();
     };
 
-    if (n_iter > 0) {
-        issue(0, false);
-        if (tid < 64) stat0[tid] = tid < 32 ? pre_stat * LOG2E : -pre_stat;
-    }
+    if (n_iter > 0) issue(0, false);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -650,6 +689,183 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_kernel(BwdKernelArgs p)
 }
 
 // ---------------------------------------------------------------------------------------
+// dQ from stored dS (the stored-dS backward).  The dK/dV kernel has written the rounded dS tiles
+// of the launch; dQ^T += K^T dS^T is then ONE GEMM per chunk pair instead of three (no S, no dP,
+// no exp).  Per chunk pair the tiles are n_q * n_k * Hq * 2 bytes, read once from HBM, which is
+// what bounds this kernel; its MFMA work is a third of bwd_dq_kernel's.
+//
+// Workgroup = 8 waves x 32 query rows of one head, as in bwd_dq_kernel.  Per 64-key tile the
+// K-NAT block is staged once for all waves (same layout, swizzle and transposing loads as above)
+// and every wave stages the four dS fragments (2 key blocks x 2 query halves) of ITS query block.
+// A stored fragment holds, per key, eight queries; the B operand of dQ^T += K^T dS^T wants, per
+// query, eight keys: the same transposing LDS load delivers that (4 keys x 16 queries per 16-lane
+// group and load).  The 16-byte piece of writer lane (key c, h') of fragment s2 is placed at
+// position 32 h' + (c ^ 4 h' ^ 8 s2) by the copy's per-lane source address, so that the 32 lanes
+// one load serves per cycle touch 32 different 8-byte bank pairs.
+template <int D>
+__global__ __launch_bounds__(NTHREAD) void bwd_dq_ds_kernel(BwdKernelArgs p)
+{
+    constexpr int DT = D / 16, DP = (D + 31) / 32 * 32, DB = DP / 32;
+    constexpr int BK = 64, KB = BK / 32;
+    constexpr int BQ = NWAVE * 32;
+    constexpr int NATF = KB * DT;            // K fragments per tile (shared by the workgroup)
+    constexpr int K_U4 = NATF * 64;
+    constexpr int K_PAD = DP > D ? 64 : 0;   // transposing loads of padded channels reach past the block
+    constexpr int DSF = KB * 2;              // dS fragments per tile and wave
+    constexpr int DS_U4 = DSF * 64;
+    constexpr int RING = 3;
+    static_assert(RING == 3, "the tile loop below is unrolled over three slots");
+    __shared__ u32x4 kring0[K_U4 + K_PAD], kring1[K_U4 + K_PAD], kring2[K_U4 + K_PAD];
+    __shared__ u32x4 dring0[NWAVE * DS_U4], dring1[NWAVE * DS_U4], dring2[NWAVE * DS_U4];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wu = __builtin_amdgcn_readfirstlane(w);
+    const int half = lane >> 5, col = lane & 31;
+    const int head = blockIdx.x % p.Hq;
+    const int n_qt = p.n_q / BQ;
+    const int qt = n_qt - 1 - (int)(blockIdx.x / p.Hq);
+    const int kvh = head / p.g;
+    const int q0 = qt * BQ, qw0 = q0 + w * 32;
+
+    const int64_t last_q_pos = p.q_pos0 + q0 + BQ - 1;
+    int64_t need = last_q_pos - p.k_pos0 + 1;
+    if (need > p.n_k) need = p.n_k;
+    if (need < 0) need = 0;
+    const int n_tiles = (int)((need + BK - 1) / BK);
+
+    const u32x4* knb = p.Knat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
+    // this wave's dS fragments: [head][query block][key block][s2][64 lanes]
+    const u32x4* dsb = p.dS + (((size_t)head * (unsigned)(p.n_q / 32) + (unsigned)(qw0 / 32)) * (unsigned)(p.n_k / 32)) * 128;
+
+    const int cp_lane0 = 32 * half + (col ^ (4 * half));  // K fragments: even index within the key block; odd: ^ 8
+    int trb[2];  // K^T: byte offsets of this lane's two transposing loads within a 32-key block
+    int dsb_off[2];  // dS^T: the same for the wave's dS fragments of one key block
+    {
+        const int grp = lane >> 4, i16 = lane & 15, e = i16 >> 2, x = i16 & 3;
+        const int h = grp >> 1, dblk = grp & 1, hq = x >> 1;
+#pragma unroll
+        for (int I = 0; I < 2; ++I)
+            trb[I] = 1024 * dblk + 512 * hq + 16 * (e + 4 * (h ^ hq) + 8 * (I ^ dblk)) + 8 * (x & 1);
+        // group (h, s2 = query half); lane i16 supplies row r = i16 / 4 (a key) and piece m = i16 % 4:
+        // writer half h' = m % 2, upper or lower 8 bytes m / 2.  Keys of a 16-key step come in the
+        // order 8 I + 4 h + r, the row order of the K^T operand above.
+        const int s2 = grp & 1, r = i16 >> 2, m = i16 & 3, hw = m & 1, up = m >> 1;
+#pragma unroll
+        for (int I = 0; I < 2; ++I)
+            dsb_off[I] = 1024 * s2 + 16 * (32 * hw + 8 * (I ^ s2) + 4 * (h ^ hw) + r) + 8 * up;
+    }
+    typedef short short4v __attribute__((ext_vector_type(4)));
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+    auto tr_frag = [&](unsigned a0, unsigned a1) -> bf16x8 {
+        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)a0);
+        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(uintptr_t)a1);
+        const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, both);
+    };
+    // source piece of this lane's LDS position in a dS fragment of query half s2
+    const int ds_src[2] = {32 * half + (col ^ (4 * half)), 32 * half + (col ^ (4 * half) ^ 8)};
+    auto issue = [&](int it, u32x4* kslot, u32x4* dslot) {
+#pragma unroll
+        for (int f0 = 0; f0 < NATF; f0 += NWAVE) {
+            const int f = f0 + wu;
+            if (f0 + NWAVE <= NATF || f < NATF) {
+                const int par = DT % 2 == 0 ? (wu & 1) : ((f % DT) & 1);
+                frag_to_lds(knb + (size_t)it * K_U4 + f * 64, kslot + f * 64, cp_lane0 ^ (8 * par));
+            }
+        }
+        u32x4* mine = dslot + wu * DS_U4;
+#pragma unroll
+        for (int f = 0; f < DSF; ++f) frag_to_lds_nt(dsb + ((size_t)it * DSF + f) * 64, mine + f * 64, ds_src[f & 1]);
+    };
+
+    floatx16 acc[DB];
+    const size_t wg = blockIdx.x;
+    float* aq = p.acc_dq + (wg * NWAVE + w) * (size_t)(DB * 16 * 64);
+    if (p.flags & ACC_LOAD) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[db][r] = aq[(db * 16 + r) * 64 + lane];
+    } else {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+    }
+
+    if (n_tiles > 0) issue(0, kring0, dring0);
+    if (n_tiles > 1) issue(1, kring1, dring1);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    const int64_t qpos_last = p.q_pos0 + qw0 + 31;
+    constexpr int NCOPY = NATF / NWAVE + DSF;  // copies EVERY wave issues per tile (some issue one more)
+    auto tile = [&](int it, const u32x4* kn, const u32x4* dsl, u32x4* pf_k, u32x4* pf_d) {
+        if (it + 2 < n_tiles) issue(it + 2, pf_k, pf_d);
+        const unsigned kn_addr = lds_address(kn);
+        const unsigned ds_addr = lds_address(dsl + wu * DS_U4);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const int64_t key0 = p.k_pos0 + (int64_t)it * BK + 32 * kb;
+            if (key0 <= qpos_last) {  // wave-uniform: the dK/dV kernel wrote exactly these blocks
+                bf16x8 bfr[2], tfr[2][DB];
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    const unsigned o = ds_addr + 2048u * (unsigned)kb + 256u * (unsigned)s2;
+                    bfr[s2] = tr_frag(o + (unsigned)dsb_off[0], o + (unsigned)dsb_off[1]);
+                }
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const unsigned o = kn_addr + 16u * 64u * (unsigned)(kb * DT) + 2048u * (unsigned)db + 256u * (unsigned)s2;
+                        tfr[s2][db] = tr_frag(o + (unsigned)trb[0], o + (unsigned)trb[1]);
+                    }
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    acc[db] = mfma32(tfr[0][db], bfr[0], acc[db]);
+                    acc[db] = mfma32(tfr[1][db], bfr[1], acc[db]);
+                }
+            }
+        }
+        if (it + 2 < n_tiles) wait_vmem_at_most<NCOPY>();
+        else wait_vmem_at_most<0>();
+        barrier_no_fence();
+    };
+    for (int it = 0; it < n_tiles; it += 3) {
+        tile(it, kring0, dring0, kring2, dring2);
+        if (it + 1 < n_tiles) tile(it + 1, kring1, dring1, kring0, dring0);
+        if (it + 2 < n_tiles) tile(it + 2, kring2, dring2, kring1, dring1);
+    }
+
+    const int row = qw0 + col;
+    if (p.flags & ACC_FINAL) {
+        store_rows_bf16<D, DB>(acc, p.scale, p.dQ + ((size_t)row * p.Hq + head) * D, half);
+    } else {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) aq[(db * 16 + r) * 64 + lane] = acc[db][r];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Row statistics in the form the dK/dV kernel consumes, so that its steps can fetch them with a
+// plain 256-byte copy: out[head][32-row block][0..31] = LSE * log2(e), [32..63] = -Delta.
+__global__ __launch_bounds__(256) void stat_pack_kernel(const float* __restrict__ LSE, const float* __restrict__ Delta,
+                                                        int64_t stride, int64_t n_blocks, int Hq,
+                                                        int64_t out_head_stride_blocks, float* __restrict__ out)
+{
+    const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // (head, block) pair
+    if (item >= n_blocks * Hq) return;
+    const int64_t head = item / n_blocks, blk = item % n_blocks;
+    const int t = threadIdx.x & 63;
+    const float v = (t < 32 ? LSE : Delta - 32)[(size_t)head * stride + blk * 32 + t];
+    out[((size_t)head * out_head_stride_blocks + blk) * 64 + t] = t < 32 ? v * LOG2E : -v;
+}
+
+// ---------------------------------------------------------------------------------------
 // Delta[h][row] = sum_d dO * O.  One wave per (row, head) pair group: lanes split channels.
 template <typename T>
 __device__ __forceinline__ float ld(const T* p);
@@ -738,12 +954,14 @@ static BwdKernelArgs to_kernel_args(const BwdArgs& a)
     k.Knat = (const u32x4*)a.Knat; k.Vnat = (const u32x4*)a.Vnat;
     k.kv_head_stride_blocks = a.kv_head_stride_blocks;
     k.LSE = a.LSE; k.Delta = a.Delta; k.row_stat_stride = a.row_stat_stride;
+    k.stat2 = a.stat2;
     k.q_pos0 = a.q_pos0; k.k_pos0 = a.k_pos0;
     k.n_q = (int)a.n_q; k.n_k = (int)a.n_k;
     k.Hq = a.Hq; k.Hkv = a.Hkv; k.g = a.Hq / a.Hkv; k.flags = a.flags;
     k.scale = a.scale; k.c = a.scale * LOG2E;
     k.acc_dq = a.acc_dq; k.acc_dk = a.acc_dk; k.acc_dv = a.acc_dv;
     k.dQ = (uint16_t*)a.dQ; k.dK = (uint16_t*)a.dK; k.dV = (uint16_t*)a.dV;
+    k.dS = (u32x4*)a.dS_frag;
     return k;
 }
 
@@ -751,9 +969,26 @@ void launch_bwd_dkdv(const BwdArgs& a, hipStream_t st)
 {
     const BwdKernelArgs k = to_kernel_args(a);
     dim3 grid((unsigned)((a.n_k / bwd_k_tile(a.D)) * a.Hkv));
-    if (a.D == 128) bwd_dkdv_kernel_w4<128><<<grid, 256, 0, st>>>(k);
-    else if (a.D == 80) bwd_dkdv_kernel_w4<80><<<grid, 256, 0, st>>>(k);
-    else bwd_dkdv_kernel_w4<64><<<grid, 256, 0, st>>>(k);
+    // (dS fragment pairs are indexed in 32 bits inside the kernels; the API layer sizes the buffer)
+    if (a.dS_frag) {
+        if (a.D == 128) bwd_dkdv_kernel_w4<128, true><<<grid, 256, 0, st>>>(k);
+        else if (a.D == 80) bwd_dkdv_kernel_w4<80, true><<<grid, 256, 0, st>>>(k);
+        else bwd_dkdv_kernel_w4<64, true><<<grid, 256, 0, st>>>(k);
+        return;
+    }
+    if (a.D == 128) bwd_dkdv_kernel_w4<128, false><<<grid, 256, 0, st>>>(k);
+    else if (a.D == 80) bwd_dkdv_kernel_w4<80, false><<<grid, 256, 0, st>>>(k);
+    else bwd_dkdv_kernel_w4<64, false><<<grid, 256, 0, st>>>(k);
+}
+
+// dQ of the launch from the dS fragments that launch_bwd_dkdv wrote for the same ranges
+void launch_bwd_dq_from_ds(const BwdArgs& a, hipStream_t st)
+{
+    const BwdKernelArgs k = to_kernel_args(a);
+    dim3 grid((unsigned)((a.n_q / bwd_q_tile(a.D)) * a.Hq));
+    if (a.D == 128) bwd_dq_ds_kernel<128><<<grid, NTHREAD, 0, st>>>(k);
+    else if (a.D == 80) bwd_dq_ds_kernel<80><<<grid, NTHREAD, 0, st>>>(k);
+    else bwd_dq_ds_kernel<64><<<grid, NTHREAD, 0, st>>>(k);
 }
 
 void launch_bwd_dq(const BwdArgs& a, hipStream_t st)
@@ -763,6 +998,15 @@ void launch_bwd_dq(const BwdArgs& a, hipStream_t st)
     if (a.D == 128) bwd_dq_kernel<128><<<grid, NTHREAD, 0, st>>>(k);
     else if (a.D == 80) bwd_dq_kernel<80><<<grid, NTHREAD, 0, st>>>(k);
     else bwd_dq_kernel<64><<<grid, NTHREAD, 0, st>>>(k);
+}
+
+void launch_stat_pack(const float* LSE, const float* Delta, int64_t stride, int64_t rows, int Hq,
+                      int64_t out_head_stride_blocks, float* out, hipStream_t st)
+{
+    const int64_t items = rows / 32 * Hq;
+    if (items <= 0) return;
+    stat_pack_kernel<<<dim3((unsigned)((items + 3) / 4)), 256, 0, st>>>(LSE, Delta, stride, rows / 32, Hq,
+                                                                       out_head_stride_blocks, out);
 }
 
 void launch_delta(const void* O, const void* dO, int64_t rows, int Hq, int D, int is_bf16,

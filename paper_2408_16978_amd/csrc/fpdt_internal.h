@@ -74,6 +74,10 @@ void launch_delta_head(const void* Q, const void* dO, const void* K, const void*
                        int64_t stat_stride, int rows, int Hq, int Hkv, int D, float scale, float* Delta,
                        hipStream_t st);
 
+// out[head][block][64] = 32 x LSE * log2(e), 32 x -Delta for `rows` query rows (multiple of 32)
+void launch_stat_pack(const float* LSE, const float* Delta, int64_t stride, int64_t rows, int Hq,
+                      int64_t out_head_stride_blocks, float* out, hipStream_t st);
+
 enum { ACC_LOAD = 1, ACC_FINAL = 2 };
 
 struct BwdArgs {
@@ -90,6 +94,9 @@ struct BwdArgs {
     const float* LSE;    // &LSE[0][q_pos0], head stride row_stat_stride (natural log)
     const float* Delta;  // &Delta[0][q_pos0], same stride
     int64_t row_stat_stride;
+    // the same statistics as the dK/dV kernel consumes them (launch_stat_pack), block 0 = rows
+    // q_pos0 .. q_pos0 + 31, head stride q_head_stride_blocks blocks of 64 floats
+    const float* stat2 = nullptr;
     int64_t q_pos0, k_pos0, n_q, n_k;
     int Hq, Hkv, D;
     float scale;
@@ -101,6 +108,9 @@ struct BwdArgs {
     void* dK;        // [n_k, Hkv, D] bf16
     void* dV;
     int flags;       // ACC_LOAD: start from the accumulators; ACC_FINAL: round + write outputs
+    // stored-dS backward: n_q * n_k * Hq bf16 of dS tiles, written by the dK/dV kernel of the
+    // launch and read by launch_bwd_dq_from_ds; null = dQ recomputes S and dP (launch_bwd_dq)
+    void* dS_frag = nullptr;
 };
 size_t bwd_acc_dq_bytes(int64_t n_q, int Hq, int D);
 size_t bwd_acc_dkv_bytes(int64_t n_k, int Hkv, int D);  // each of dK, dV
@@ -108,6 +118,8 @@ int bwd_k_tile(int D);
 int bwd_q_tile(int D);
 void launch_bwd_dkdv(const BwdArgs& a, hipStream_t st);
 void launch_bwd_dq(const BwdArgs& a, hipStream_t st);
+void launch_bwd_dq_from_ds(const BwdArgs& a, hipStream_t st);
+static inline size_t bwd_ds_bytes(int64_t n_q, int64_t n_k, int Hq) { return (size_t)n_q * (size_t)n_k * Hq * 2; }
 
 // ---------------------------------------------------------------------------
 // fp32 path (accuracy path; plain FMA, one wave per row)

@@ -84,6 +84,21 @@ __device__ __forceinline__ void frag_to_lds(const u32x4* src_wave_uniform, u32x4
                  : "memory");  // m0 is reserved: the compiler sets it right before each use of its own
 }
 
+// The same copy with the non-temporal hint: for operands that are read once and must not push
+// the tiles other workgroups share out of L2.
+__device__ __forceinline__ void frag_to_lds_nt(const u32x4* src_wave_uniform, u32x4* dst_wave_uniform, int lane)
+{
+    const unsigned lds = __builtin_amdgcn_readfirstlane(
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)dst_wave_uniform);
+    const uint64_t a = (uint64_t)(uintptr_t)src_wave_uniform;
+    const uint64_t src = ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(a >> 32)) << 32) |
+                         (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)a);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 :
+                 : "s"(lds), "v"(lane * 16), "s"(src)
+                 : "memory");
+}
+
 // The same copy for callers that already hold both addresses in scalar registers (values that
 // came out of uniform()): no address arithmetic in vector registers at the point of issue.
 // lds_addr is the byte address within LDS, lane16 = 16 * lane.
@@ -101,6 +116,16 @@ __device__ __forceinline__ void frag_to_lds_at(uint64_t src_uniform, unsigned ld
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_addr_uniform), "v"(lane16), "s"(src_uniform)
+                 : "memory");
+}
+
+// 256 bytes (one dword per lane) global -> LDS the same way: lane l's dword, read from
+// src + lane4, lands at lds_addr + 4 l.  lane4 = 4 * lane.
+__device__ __forceinline__ void dwords_to_lds_at(uint64_t src_uniform, unsigned lds_addr_uniform, int lane4)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :
+                 : "s"(lds_addr_uniform), "v"(lane4), "s"(src_uniform)
                  : "memory");
 }
 

@@ -22,6 +22,9 @@ class Config:
     dtype: str          # "f32" | "bf16"
     kv_on_host: bool = False
     act_on_host: bool = False
+    # backward from stored dS tiles (FPDT_BWD_STORE_DS): 5 executed GEMMs per chunk pair instead
+    # of 7, for chunk^2 * Hq * 2 bytes of workspace
+    store_ds: bool = False
 
     @property
     def u(self) -> int:
@@ -47,10 +50,12 @@ CONFIGS = {
     "gpt2p7b_64k": Config("gpt2p7b_64k", 65536, 8192, 4, 4, 80, "bf16"),
     # profiling-sized cut of the Llama-8B head share: one chunk, same kernels and tiles
     "llama8b_64k": Config("llama8b_64k", 65536, 65536, 8, 2, 128, "bf16"),
-    "llama8b_256k": Config("llama8b_256k", 262144, 65536, 8, 2, 128, "bf16"),
-    "llama8b_2m": Config("llama8b_2m", 2097152, 65536, 8, 2, 128, "bf16", kv_on_host=True),
+    "llama8b_256k": Config("llama8b_256k", 262144, 65536, 8, 2, 128, "bf16", store_ds=True),
+    # the same workload in the one-launch-per-kernel form (dQ recomputes S and dP)
+    "llama8b_256k_one_launch": Config("llama8b_256k_one_launch", 262144, 65536, 8, 2, 128, "bf16"),
+    "llama8b_2m": Config("llama8b_2m", 2097152, 65536, 8, 2, 128, "bf16", kv_on_host=True, store_ds=True),
     "llama70b_1m": Config("llama70b_1m", 1048576, 65536, 8, 1, 128, "bf16", kv_on_host=True,
-                          act_on_host=True),
+                          act_on_host=True, store_ds=True),
 }
 
 _TENSOR_IDS = {"Q": 0, "K": 1, "V": 2, "dO": 3}

@@ -54,7 +54,7 @@ def make_buffers(Q, K, V, dO, chunk, scale, flags=0, bwd=True, chunk_mask=None) 
     kvh = bool(flags & B.FPDT_KV_ON_HOST)
     acth = bool(flags & B.FPDT_ACT_ON_HOST)
     dt = B.FPDT_DTYPE_BF16 if Q.dtype == torch.bfloat16 else B.FPDT_DTYPE_F32
-    fwd_flags = flags & ~(B.FPDT_BWD_KV_OUTER | B.FPDT_BWD_Q_OUTER)
+    fwd_flags = flags & ~(B.FPDT_BWD_KV_OUTER | B.FPDT_BWD_Q_OUTER | B.FPDT_BWD_STORE_DS)
     bufs = Buffers(
         Q=_place(Q, acth), K=_place(K, kvh), V=_place(V, kvh), dO=_place(dO, acth),
         O=_empty_like_placed((S, Hq, D), Q.dtype, acth),
@@ -69,7 +69,7 @@ def make_buffers(Q, K, V, dO, chunk, scale, flags=0, bwd=True, chunk_mask=None) 
 
 
 def forward(b: Buffers, stream=None):
-    fwd_flags = b.flags & ~(B.FPDT_BWD_KV_OUTER | B.FPDT_BWD_Q_OUTER)
+    fwd_flags = b.flags & ~(B.FPDT_BWD_KV_OUTER | B.FPDT_BWD_Q_OUTER | B.FPDT_BWD_STORE_DS)
     if b.chunk_mask is not None:
         B.fpdt_attn_fwd_blocksparse(b.Q, b.K, b.V, b.O, b.LSE, b.chunk, b.scale, b.chunk_mask,
                                     fwd_flags, b.ws_fwd, stream)

@@ -42,7 +42,7 @@ def test_binding_names_match_header():
 def test_header_constants_match_binding():
     text = open(os.path.join(ROOT, "include", "fpdt.h")).read()
     for name in ("FPDT_KV_ON_HOST", "FPDT_ACT_ON_HOST", "FPDT_BWD_KV_OUTER", "FPDT_BWD_Q_OUTER",
-                 "FPDT_PAIRWISE"):
+                 "FPDT_PAIRWISE", "FPDT_BWD_STORE_DS"):
         m = re.search(name + r"\s*=\s*1u\s*<<\s*(\d+)", text)
         assert m and getattr(B, name) == 1 << int(m.group(1)), name
     assert re.search(r"FPDT_CHUNK_MULTIPLE\s*=\s*256", text) and B.FPDT_CHUNK_MULTIPLE == 256
@@ -112,6 +112,13 @@ def test_workspace_sizes():
         assert grow == ws(S2, 65536, 8, 2, 128, bf, kvh | B.FPDT_BWD_KV_OUTER, True) - ws(S1, 65536, 8, 2, 128, bf, kvh | B.FPDT_BWD_KV_OUTER, True)
         grow_q = ws(S2, 65536, 8, 2, 128, bf, kvh | B.FPDT_BWD_Q_OUTER, True) - ws(S1, 65536, 8, 2, 128, bf, kvh | B.FPDT_BWD_Q_OUTER, True)
         assert grow_q == (S2 - S1) * (2 * 2 * 128 + 8) * 4
+    # stored-dS backward: the dS tiles of one chunk pair on top of the pair-by-pair workspace; the
+    # forward ignores the flag
+    sd = B.FPDT_BWD_STORE_DS
+    assert ws(1 << 21, 65536, 8, 2, 128, bf, kvh | sd, True) - ws(1 << 21, 65536, 8, 2, 128, bf, kvh, True) == 65536 * 65536 * 8 * 2
+    assert ws(1 << 16, 8192, 4, 4, 80, bf, sd, True) - ws(1 << 16, 8192, 4, 4, 80, bf, B.FPDT_PAIRWISE, True) == 8192 * 8192 * 4 * 2
+    assert ws(1 << 21, 65536, 8, 2, 128, bf, kvh | sd, False) == ws(1 << 21, 65536, 8, 2, 128, bf, kvh, False)
+    assert ws(1024, 256, 2, 2, 64, B.FPDT_DTYPE_F32, sd, True) == 0              # fp32: unsupported
     # at the headline workload: 8 GiB + 64 MiB of S-sized state under KV-outer, 2 GiB + 64 MiB under Q-outer
     assert ws(1 << 21, 65536, 8, 2, 128, bf, kvh, True) - ws(1 << 21, 65536, 8, 2, 128, bf, kvh | B.FPDT_BWD_Q_OUTER, True) \
         == (1 << 21) * 8 * 128 * 4 - 2 * (1 << 21) * 2 * 128 * 4 - (65536 * 8 * 128 * 4 - 2 * 65536 * 2 * 128 * 4)

@@ -39,7 +39,8 @@ def gpu_run(name, seed=7):
         cfg = inputs.CONFIGS[name]
         print("[case]", cfg, flush=True)
         Q, K, V, dO = inputs.make_qkvdo(cfg.S, cfg.Hq, cfg.Hkv, cfg.D, cfg.dtype, seed, device="cuda")
-        flags = (B.FPDT_KV_ON_HOST if cfg.kv_on_host else 0) | (B.FPDT_ACT_ON_HOST if cfg.act_on_host else 0)
+        flags = (B.FPDT_KV_ON_HOST if cfg.kv_on_host else 0) | (B.FPDT_ACT_ON_HOST if cfg.act_on_host else 0) | \
+            (B.FPDT_BWD_STORE_DS if cfg.store_ds else 0)   # the launch configuration bench.py times
         b = runner.make_buffers(Q, K, V, dO, cfg.chunk, cfg.scale, flags)
         runner.forward(b)
         runner.backward(b)
@@ -167,8 +168,8 @@ def check_invariants(name):
 
 # (workload, random rows, unconditional tail keys, random key rows per chunk); the three checks of
 # a workload run back to back on one forward + backward
-LARGE = [("gpt2p7b_64k", 48, 64, 8), ("llama8b_256k", 48, 32, 16), ("llama70b_1m", 24, 16, 3),
-         ("llama8b_2m", 16, 8, 2)]
+LARGE = [("gpt2p7b_64k", 48, 64, 8), ("llama8b_256k", 48, 32, 16), ("llama8b_256k_one_launch", 24, 16, 4),
+         ("llama70b_1m", 24, 16, 3), ("llama8b_2m", 16, 8, 2)]
 CASES = [(name, kind, n_random, tail, per_chunk) for name, n_random, tail, per_chunk in LARGE
          for kind in ("rows", "columns", "invariants")]
 

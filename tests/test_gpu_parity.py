@@ -75,6 +75,38 @@ def test_bf16_pairwise_full(Hq, Hkv, D, order):
     print(parity.check_all(out, ref, True))
 
 
+@pytest.mark.parametrize("Hq,Hkv,D", SHAPES)
+@pytest.mark.parametrize("order", [B.FPDT_BWD_KV_OUTER, B.FPDT_BWD_Q_OUTER])
+def test_bf16_stored_ds_backward(Hq, Hkv, D, order):
+    """FPDT_BWD_STORE_DS: the dK/dV kernel writes its dS tiles and dQ is one GEMM over them.
+    dK and dV must be the bits of the recomputing schedule (same kernel arithmetic, plus stores);
+    dQ is checked against the oracle like any other dQ."""
+    S, chunk = 2048, 256
+    announce("bf16 stored dS", S, chunk, Hq, Hkv, D, order)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=14)
+    scale = D ** -0.5
+    ref = parity.oracle_full(Q, K, V, dO, scale)
+    base = run(Q, K, V, dO, chunk, scale, B.FPDT_PAIRWISE | order)
+    out = run(Q, K, V, dO, chunk, scale, B.FPDT_BWD_STORE_DS | order)
+    for n in ("O", "LSE", "dK", "dV"):
+        assert torch.equal(out[n], base[n]), n
+    print(parity.check_all(out, ref, True))
+
+
+@pytest.mark.parametrize("S,chunk,Hq,Hkv,D,flags", [
+    (768, 256, 4, 4, 128, 0), (1280, 1280, 8, 2, 128, 0), (2304, 768, 4, 4, 80, 0), (2304, 768, 2, 1, 64, 0),
+    (4096, 512, 8, 2, 128, B.FPDT_KV_ON_HOST), (4096, 512, 8, 1, 128, B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST)])
+def test_bf16_stored_ds_odd_sizes_and_offload(S, chunk, Hq, Hkv, D, flags):
+    """Stored-dS backward at odd multiples of the tile size, as a single chunk, and under the
+    offload pipelines (K/V on the host in the paper's loop order; everything on the host, Q-outer)."""
+    announce("bf16 stored dS", S, chunk, Hq, Hkv, D, flags)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=15)
+    scale = D ** -0.5
+    ref = parity.oracle_full(Q, K, V, dO, scale)
+    out = run(Q, K, V, dO, chunk, scale, flags | B.FPDT_BWD_STORE_DS)
+    print(parity.check_all(out, ref, True))
+
+
 @pytest.mark.parametrize("S,chunk", [(768, 256), (1280, 1280), (2304, 768)])
 @pytest.mark.parametrize("Hq,Hkv,D", [(4, 4, 128), (8, 2, 128), (4, 4, 80), (2, 1, 64)])
 def test_bf16_odd_tile_counts_and_ungrouped_heads(S, chunk, Hq, Hkv, D):
