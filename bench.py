@@ -199,7 +199,7 @@ def main():
     # code-object load and first-launch costs are paid on a small problem of the same kernels
     if cfg.dtype == "bf16":
         w = inputs.make_qkvdo(1024, cfg.Hq, cfg.Hkv, cfg.D, "bf16", 1, device="cuda")
-        wb = runner.make_buffers(*w, 256, cfg.scale, B.FPDT_PAIRWISE)
+        wb = runner.make_buffers(*w, 256, cfg.scale, B.FPDT_PAIRWISE | (flags & B.FPDT_BWD_STORE_DS))
         runner.forward(wb)
         runner.backward(wb)
         torch.cuda.synchronize()
@@ -292,6 +292,18 @@ def main():
                 "avg_launch_ms": prof[dom]["total_ms"] / max(1, prof[dom]["launches"]),
                 "launches": prof[dom]["launches"]}
 
+    roofline_dq = None
+    if store_ds and prof["bwd_dq"]["total_ms"] > 0:
+        # the dQ kernel of the stored-dS backward reads every dS tile of the causal triangle once
+        # (bf16, Hq heads): its algorithmic bytes; it is bound by HBM, not by the MFMA pipe
+        ds_bytes = 2.0 * cfg.Hq * cfg.S * (cfg.S + 1) / 2.0 * pair_frac * args.steps
+        gbps = ds_bytes / (prof["bwd_dq"]["total_ms"] * 1e-3) / 1e9
+        roofline_dq = {"bound": "hbm", "kernel": "bwd_dq (from stored dS)", "achieved": gbps, "peak": 8000.0,
+                       "unit": "GB/s", "frac": gbps / 8000.0,
+                       "traffic": hbm_traffic_per_launch(cfg.name, "bwd_dq"),
+                       "avg_launch_ms": prof["bwd_dq"]["total_ms"] / max(1, prof["bwd_dq"]["launches"]),
+                       "launches": prof["bwd_dq"]["launches"]}
+
     out = {
         "metric": "chunked causal attn fwd+bwd TFLOPS",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": warm_done,
@@ -310,6 +322,8 @@ def main():
         "kernels": prof,
         "roofline": roofline,
     }
+    if roofline_dq is not None:
+        out["roofline_dq"] = roofline_dq
     if link[0] or link[1]:
         off = {"h2d_bytes_per_step": link[0] / args.steps, "d2h_bytes_per_step": link[1] / args.steps}
         if prof["h2d"]["total_ms"] > 0:
