@@ -433,8 +433,9 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
                     constexpr int EVERY = 2 * DB >= 8 ? 2 : 1;
                     if (i % EVERY == 0 && i / EVERY < 4) {
                         const int f = i / EVERY;
-                        asm volatile("global_store_dwordx4 %0, %1, %2 nt"
-                                     :
+                        uint64_t addr;  // address through a scalar move: copy_address_rule in mfma_tiles.h
+                        asm volatile("s_mov_b64 %0, %3\n\tglobal_store_dwordx4 %1, %2, %0 nt"
+                                     : "=&s"(addr)
                                      : "v"(lane * 16), "v"(__builtin_bit_cast(u32x4, df[f / 2][f % 2])),
                                        "s"(ds_dst + 1024u * (unsigned)f)
                                      : "memory");
@@ -735,7 +736,7 @@ __global__ __launch_bounds__(NTHREAD) void bwd_dq_ds_kernel(BwdKernelArgs p)
 
     const u32x4* knb = p.Knat + (size_t)kvh * p.kv_head_stride_blocks * (DT * 64);
     // this wave's dS fragments: [head][query block][key block][s2][64 lanes]
-    const u32x4* dsb = p.dS + (((size_t)head * (unsigned)(p.n_q / 32) + (unsigned)(qw0 / 32)) * (unsigned)(p.n_k / 32)) * 128;
+    const u32x4* dsb = p.dS + (((size_t)head * (unsigned)(p.n_q / 32) + (unsigned)(q0 / 32 + wu)) * (unsigned)(p.n_k / 32)) * 128;
 
     const int cp_lane0 = 32 * half + (col ^ (4 * half));  // K fragments: even index within the key block; odd: ^ 8
     int trb[2];  // K^T: byte offsets of this lane's two transposing loads within a 32-key block

@@ -70,6 +70,14 @@ __device__ __forceinline__ void barrier_no_fence()
 // callers drain it with wait_vmem_at_most<N>() before the barrier that publishes the tile.
 // (Waits the compiler computes for its own vector loads then count too few operations in
 // flight, which only makes them stricter.)
+//
+// copy_address_rule.  A vector-memory instruction that reads its address from scalar registers
+// must not follow, within five wait states, a VECTOR instruction that wrote those registers
+// (v_readfirstlane_b32 is one).  The compiler keeps that distance for its own instructions; it
+// cannot see into inline assembly.  So the copy never reads the caller's registers directly: a
+// scalar move takes the address into a register pair of the statement's own first (scalar reads of
+// vector-written scalar registers are interlocked by the hardware), and the copy reads that pair.
+// The same move is the wait state that the write of M0 needs in front of an LDS-DMA instruction.
 __device__ __forceinline__ void frag_to_lds(const u32x4* src_wave_uniform, u32x4* dst_wave_uniform, int lane)
 {
     const unsigned lds = __builtin_amdgcn_readfirstlane(
@@ -78,8 +86,9 @@ __device__ __forceinline__ void frag_to_lds(const u32x4* src_wave_uniform, u32x4
     // (readfirstlane returns a signed int: widen each half as unsigned)
     const uint64_t src = ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(a >> 32)) << 32) |
                          (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)a);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
+    uint64_t addr;  // see copy_address_rule below
+    asm volatile("s_mov_b32 m0, %1\n\ts_mov_b64 %0, %3\n\tglobal_load_lds_dwordx4 %2, %0"
+                 : "=&s"(addr)
                  : "s"(lds), "v"(lane * 16), "s"(src)
                  : "memory");  // m0 is reserved: the compiler sets it right before each use of its own
 }
@@ -93,8 +102,9 @@ __device__ __forceinline__ void frag_to_lds_nt(const u32x4* src_wave_uniform, u3
     const uint64_t a = (uint64_t)(uintptr_t)src_wave_uniform;
     const uint64_t src = ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(a >> 32)) << 32) |
                          (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)a);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
-                 :
+    uint64_t addr;
+    asm volatile("s_mov_b32 m0, %1\n\ts_mov_b64 %0, %3\n\tglobal_load_lds_dwordx4 %2, %0 nt"
+                 : "=&s"(addr)
                  : "s"(lds), "v"(lane * 16), "s"(src)
                  : "memory");
 }
@@ -113,8 +123,9 @@ __device__ __forceinline__ unsigned lds_address(const void* p)
 }
 __device__ __forceinline__ void frag_to_lds_at(uint64_t src_uniform, unsigned lds_addr_uniform, int lane16)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
+    uint64_t addr;
+    asm volatile("s_mov_b32 m0, %1\n\ts_mov_b64 %0, %3\n\tglobal_load_lds_dwordx4 %2, %0"
+                 : "=&s"(addr)
                  : "s"(lds_addr_uniform), "v"(lane16), "s"(src_uniform)
                  : "memory");
 }
@@ -123,8 +134,9 @@ __device__ __forceinline__ void frag_to_lds_at(uint64_t src_uniform, unsigned ld
 // src + lane4, lands at lds_addr + 4 l.  lane4 = 4 * lane.
 __device__ __forceinline__ void dwords_to_lds_at(uint64_t src_uniform, unsigned lds_addr_uniform, int lane4)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :
+    uint64_t addr;
+    asm volatile("s_mov_b32 m0, %1\n\ts_mov_b64 %0, %3\n\tglobal_load_lds_dword %2, %0"
+                 : "=&s"(addr)
                  : "s"(lds_addr_uniform), "v"(lane4), "s"(src_uniform)
                  : "memory");
 }

@@ -60,6 +60,22 @@ def test_bf16_blocksparse(Hq, Hkv, D, order):
     print(parity.check_all(out, ref, True))
 
 
+@pytest.mark.parametrize("Hq,Hkv,D,order", [(8, 2, 128, B.FPDT_BWD_KV_OUTER), (4, 4, 80, B.FPDT_BWD_Q_OUTER)])
+def test_bf16_blocksparse_with_stored_ds(Hq, Hkv, D, order):
+    """The stored-dS backward under a chunk mask: the pairs that are kept write and read their dS
+    tiles, the others do neither; dK and dV are the bits of the recomputing schedule."""
+    S, chunk = 2048, 256
+    print("[case] bf16 block-sparse, stored dS", S, chunk, Hq, Hkv, D, order, flush=True)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=27)
+    mask = chunk_mask(S // chunk, 28)
+    ref = oracle(Q, K, V, dO, D ** -0.5, chunk, mask)
+    base = run(Q, K, V, dO, chunk, D ** -0.5, mask, order)
+    out = run(Q, K, V, dO, chunk, D ** -0.5, mask, order | B.FPDT_BWD_STORE_DS)
+    for n in ("dK", "dV"):
+        assert torch.equal(out[n], base[n]), n
+    print(parity.check_all(out, ref, True))
+
+
 def test_all_ones_mask_is_bitwise_the_pairwise_dense_path():
     S, chunk, Hq, Hkv, D = 2048, 256, 8, 2, 128
     print("[case] all-ones mask vs pairwise dense", flush=True)
