@@ -224,23 +224,40 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel_w4(BwdKernelArgs p)
         for (int I = 0; I < 2; ++I)
             trb[I] = 1024 * dblk + 512 * hq + 16 * (e + 4 * (h ^ hq) + 8 * (I ^ dblk)) + 8 * (x & 1);
     }
+    // issue_begin(it) sets the scalar source addresses of step `it`: block (head, qb) with
+    // hh = it % g, qb = n_qb_all - 1 - it / g, head = kvh g + hh.  It is called for it = 0, 1, 2, ..
+    // in order (and once more for the last step), so the addresses are advanced by one of two
+    // precomputed strides instead of being rebuilt: no division, no vector instruction, a dozen
+    // scalar instructions at the head of a step, where nothing hides them.
+    const int w64 = DT == 8 ? wu * 64 : 0;  // D = 128: the wave's first fragment of each operand
+    const int64_t blk_next_head = p.q_head_stride_blocks;                          // hh + 1, same qb
+    const int64_t blk_next_qb = -(int64_t)(p.g - 1) * p.q_head_stride_blocks - 1;  // hh wraps to 0, qb - 1
+    const int64_t pair_next_head = (int64_t)n_qb_all * (p.n_k / 32);
+    const int64_t pair_next_qb = -(int64_t)(p.g - 1) * pair_next_head - (p.n_k / 32);
+    int st_it = 0, st_hh = 0;  // the step the addresses below belong to, and its head within the group
+    {
+        const int64_t blk0 = (int64_t)(kvh * p.g) * p.q_head_stride_blocks + (n_qb_all - 1);
+        cp_src[0] = (uint64_t)(uintptr_t)(p.Qnat + blk0 * NAT_U4 + w64);
+        cp_src[1] = (uint64_t)(uintptr_t)(p.dOnat + blk0 * NAT_U4 + w64);
+        stat_src = (uint64_t)(uintptr_t)(p.stat2 + blk0 * 64);
+        if constexpr (STORE_DS) {
+            // fragment pairs (head, query block, key block) of a launch are fewer than 2^31 (API layer)
+            const int64_t pair0 = ((int64_t)(kvh * p.g) * n_qb_all + (n_qb_all - 1)) * (p.n_k / 32) + kw0 / 32;
+            ds_next = (uint64_t)(uintptr_t)p.dS + ((uint64_t)pair0 << 11);
+        }
+    }
     auto issue_begin = [&](int it) {
-        const int hh = it % p.g, qb = n_qb_all - 1 - it / p.g;
-        const int head = kvh * p.g + hh;
-        const size_t blk = (size_t)head * p.q_head_stride_blocks + qb;
-        const int w64 = DT == 8 ? wu * 64 : 0;  // D = 128: the wave's first fragment of each operand
-        cp_src[0] = uniform((uint64_t)(uintptr_t)(p.Qnat + blk * NAT_U4 + w64));
-        cp_src[1] = uniform((uint64_t)(uintptr_t)(p.dOnat + blk * NAT_U4 + w64));
+        if (it == st_it) return;  // the first step, and the last step's second request
+        st_it = it;
+        const bool wrap = ++st_hh == p.g;
+        if (wrap) st_hh = 0;
+        const int64_t db = wrap ? blk_next_qb : blk_next_head;
+        cp_src[0] += (uint64_t)(db * (int64_t)(NAT_U4 * 16));
+        cp_src[1] += (uint64_t)(db * (int64_t)(NAT_U4 * 16));
         // the block's row statistics (256 bytes, already in the form the step consumes) travel
         // through the copy engine like the operands: no vector register, no wait of the compiler's
-        stat_src = uniform((uint64_t)(uintptr_t)(p.stat2 + blk * 64));
-        if constexpr (STORE_DS) {
-            // fragment pair index of (head, query block, this wave's first key block) in 32 bits (the
-            // API layer keeps a launch below 2^31 of them); computed here, beside the other scalar
-            // address work of the step's head, so that nothing but the stores sits among the MFMAs
-            const unsigned pair = uniform(((unsigned)head * (unsigned)n_qb_all + (unsigned)qb) * (unsigned)(p.n_k / 32) + (unsigned)(kw0 / 32));
-            ds_next = (uint64_t)(uintptr_t)p.dS + ((uint64_t)pair << 11);
-        }
+        stat_src += (uint64_t)(db * 256);
+        if constexpr (STORE_DS) ds_next += (uint64_t)((wrap ? pair_next_qb : pair_next_head) * 2048);
     };
     // k = 0..3 (compile-time after unrolling): fragment 4 k + w of the step, i.e. fragment
     // 4 (k % 2) + w of operand k / 2; into_slot1 is a compile-time constant at every call
