@@ -148,3 +148,13 @@ def test_pick_chunk_host_logic(lib):
     assert B.fpdt_attn_pick_chunk(0, 2, 2, 64, BF) == 0 and B.fpdt_last_error() != ""
     assert B.fpdt_attn_pick_chunk(4096, 3, 2, 64, BF) == 0 and "Hq" in B.fpdt_last_error()
     assert B.fpdt_attn_pick_chunk(4096, 2, 2, 64, BF, 0, 16) == 0 and "workspace" in B.fpdt_last_error()
+
+
+def test_calibration_arguments_are_checked_without_a_gpu(lib):
+    tf = ctypes.c_double(0.0)
+    assert lib.fpdt_calibrate_mfma(99, 1000, None, 0, ctypes.byref(tf), None, None) == B.FPDT_ERR_INVALID_ARG
+    assert "kind" in B.fpdt_last_error()
+    assert lib.fpdt_calibrate_mfma(0, 0, None, 0, ctypes.byref(tf), None, None) == B.FPDT_ERR_INVALID_ARG
+    assert lib.fpdt_calibrate_mfma(0, 1000, None, 0, None, None, None) == B.FPDT_ERR_INVALID_ARG
+    assert lib.fpdt_calibrate_mfma(0, 1000, None, 0, ctypes.byref(tf), None, None) == B.FPDT_ERR_WORKSPACE
+    assert len(B.FPDT_CAL_KINDS) == 8

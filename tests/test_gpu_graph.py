@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("flags", [0, B.FPDT_PAIRWISE | B.FPDT_BWD_KV_OUTER, B.FPDT_KV_ON_HOST,
                                    B.FPDT_KV_ON_HOST | B.FPDT_BWD_Q_OUTER,
-                                   B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST])
+                                   B.FPDT_KV_ON_HOST | B.FPDT_ACT_ON_HOST,
+                                   B.FPDT_KV_ON_HOST | B.FPDT_BWD_STORE_DS])
 def test_forward_and_backward_replay_from_a_graph(flags):
     S, chunk, Hq, Hkv, D = 2304, 256, 8, 2, 128  # nine chunks: every staging buffer is reused
     print("[case] graph capture", S, chunk, Hq, Hkv, D, flags, flush=True)

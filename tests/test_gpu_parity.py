@@ -255,3 +255,13 @@ def test_invalid_pointers_are_rejected_on_gpu():
         B.fpdt_attn_fwd(b.Q, b.K, b.V, b.O, b.LSE, chunk, D ** -0.5, B.FPDT_KV_ON_HOST,
                         B.alloc_workspace(S, chunk, Hq, Hkv, D, B.FPDT_DTYPE_BF16, B.FPDT_KV_ON_HOST))
     assert e.value.status == B.FPDT_ERR_INVALID_ARG
+
+
+def test_calibration_loops_report_plausible_rates():
+    """fpdt_calibrate_mfma: every loop runs and the rates are ordered as the hardware orders them
+    (MFMAs alone fastest; LDS-fed operands plus the softmax's vector work slowest), inside the
+    range a 2.5 PFLOP/s part can deliver."""
+    rates = [B.fpdt_calibrate_mfma(kind, 2000)[0] for kind in range(len(B.FPDT_CAL_KINDS))]
+    announce("calibration", dict(zip(B.FPDT_CAL_KINDS, (round(r) for r in rates))))
+    assert all(300.0 < r < 2600.0 for r in rates)
+    assert rates[0] > rates[2] > rates[6] and rates[0] > rates[4] > rates[6] and rates[1] > rates[7]
