@@ -173,40 +173,57 @@ __global__ __launch_bounds__(NTHREAD) void fwd_sweep_kernel(FwdKernelArgs p)
                     for (int r = 0; r < 16; ++r)
                         if (32 * kb + 8 * (r >> 2) + (r & 3) > rel) s[kb][r] = -INFINITY;
             }
-            float mx = fmaxf(s[0][0], s[0][1]);
+            // The running maximum is only a reference point: any value gives the same O and LSE as
+            // long as nothing overflows.  So the tile is exponentiated against the reference it
+            // found, optimistically, and no maximum is taken at all; the row sums that are needed
+            // anyway tell when that was wrong: every probability is at most the partial sum it
+            // went into, so a sum within REF_LIMIT (far inside the range of bf16 and of the fp32
+            // sums) proves that no probability exceeded it.  A sum beyond it -- or infinite, or not
+            // a number, as on a row's first tile, where the reference is still -inf -- sends the
+            // whole wave through the exact path below (true maximum, rescale, exponentiate again):
+            // a row's first tile, and later only when its maximum rises by more than 14 in log2.
+            constexpr float REF_LIMIT = 16384.f;
+            bf16x8 pf[KB][2];
+            float lsum = 0.f;
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
+            for (int kb = 0; kb < KB; ++kb) {
+                floatx16 e;
 #pragma unroll
-                for (int r = (kb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[kb][r]), s[kb][r + 1]);
-            mx = fmaxf(mx, xor32(mx));
-            // The running maximum is only a reference point (any value gives the same O and LSE as
-            // long as nothing overflows): it follows the true maximum only when that has risen by
-            // more than 8 (a factor 256 in the probabilities, far inside the range of bf16 and of
-            // the fp32 sums), so the rescale below is rare even while the maxima still creep up.
-            const float mc = mx * p.c;
-            const float m_new = mc > m_run + 8.f ? mc : m_run;
-            // Rescale only when some query of the wave raised its maximum.
-            if (__any(m_new != m_run)) {
-                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                for (int r = 0; r < 16; ++r) {
+                    e[r] = __builtin_amdgcn_exp2f(fmaf(s[kb][r], p.c, -m_run));
+                    lsum += e[r];
+                }
+                pf[kb][0] = pack_half<0>(e);
+                pf[kb][1] = pack_half<1>(e);
+            }
+            if (__any(!(lsum <= REF_LIMIT))) {
+                float mx = fmaxf(s[0][0], s[0][1]);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int r = (kb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[kb][r]), s[kb][r + 1]);
+                mx = fmaxf(mx, xor32(mx));
+                const float mc = mx * p.c;
+                const float m_new = mc > m_run ? mc : m_run;  // (a lane whose keys are all masked keeps its reference)
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on a row's first tile, 1 where nothing moved
                 l_run *= alpha;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[db][r] *= alpha;
                 m_run = m_new;
-            }
-            bf16x8 pf[KB][2];
-            float lsum = 0.f;
+                lsum = 0.f;
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
+                for (int kb = 0; kb < KB; ++kb) {
+                    floatx16 e;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float e = __builtin_amdgcn_exp2f(fmaf(s[kb][r], p.c, -m_new));
-                    s[kb][r] = e;
-                    lsum += e;
+                    for (int r = 0; r < 16; ++r) {
+                        e[r] = __builtin_amdgcn_exp2f(fmaf(s[kb][r], p.c, -m_new));
+                        lsum += e[r];
+                    }
+                    pf[kb][0] = pack_half<0>(e);
+                    pf[kb][1] = pack_half<1>(e);
                 }
-                pf[kb][0] = pack_half<0>(s[kb]);
-                pf[kb][1] = pack_half<1>(s[kb]);
             }
             l_run += lsum;
             // ---- O^T += V^T P^T ----
