@@ -73,6 +73,13 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     assert _fwd(lib, S=1000, chunk=100) == B.FPDT_ERR_UNSUPPORTED           # bf16 chunk % 256
     assert _fwd(lib, dtype=B.FPDT_DTYPE_F32, flags=B.FPDT_KV_ON_HOST) == B.FPDT_ERR_UNSUPPORTED
     assert _fwd(lib, flags=B.FPDT_ACT_ON_HOST | B.FPDT_BWD_KV_OUTER) == B.FPDT_ERR_UNSUPPORTED
+    # the stored-dS backward: bf16 only (the forward ignores the flag), and a chunk whose dS tiles
+    # could not be indexed is refused
+    bwd = lambda **kw: lib.fpdt_attn_bwd(*([0x1000] * 9), kw.get("S", 1024), kw.get("chunk", 256), 2, 2, 64, 0.125,
+                                         kw.get("dtype", B.FPDT_DTYPE_BF16), kw.get("flags", 0), 0x100000, 1 << 40, None)
+    assert bwd(dtype=B.FPDT_DTYPE_F32, flags=B.FPDT_BWD_STORE_DS) == B.FPDT_ERR_UNSUPPORTED
+    assert "stored-dS" in B.fpdt_last_error()
+    assert bwd(S=1 << 22, chunk=1 << 21, flags=B.FPDT_BWD_STORE_DS) == B.FPDT_ERR_UNSUPPORTED
     assert _fwd(lib, ws=None) == B.FPDT_ERR_WORKSPACE
     assert _fwd(lib, ws_bytes=16) == B.FPDT_ERR_WORKSPACE
     assert _fwd(lib, ws=0x100010) == B.FPDT_ERR_WORKSPACE                    # misaligned
