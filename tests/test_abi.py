@@ -80,6 +80,11 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     assert bwd(dtype=B.FPDT_DTYPE_F32, flags=B.FPDT_BWD_STORE_DS) == B.FPDT_ERR_UNSUPPORTED
     assert "stored-dS" in B.fpdt_last_error()
     assert bwd(S=1 << 22, chunk=1 << 21, flags=B.FPDT_BWD_STORE_DS) == B.FPDT_ERR_UNSUPPORTED
+    # sizes beyond the 32-bit launch arithmetic are refused, the largest supported one is accepted
+    # as far as the scalar checks go (it then fails on the fake pointers, not on its size)
+    assert _fwd(lib, S=(1 << 30) + 256, chunk=256) == B.FPDT_ERR_UNSUPPORTED and "launch limits" in B.fpdt_last_error()
+    assert _fwd(lib, S=1 << 30, chunk=1 << 20, Hq=64, Hkv=8) == B.FPDT_ERR_UNSUPPORTED
+    assert B.fpdt_attn_workspace_bytes(1 << 30, 1 << 16, 8, 2, 128, B.FPDT_DTYPE_BF16, B.FPDT_KV_ON_HOST, False) > 0
     assert _fwd(lib, ws=None) == B.FPDT_ERR_WORKSPACE
     assert _fwd(lib, ws_bytes=16) == B.FPDT_ERR_WORKSPACE
     assert _fwd(lib, ws=0x100010) == B.FPDT_ERR_WORKSPACE                    # misaligned
