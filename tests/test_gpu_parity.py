@@ -261,7 +261,7 @@ def test_calibration_loops_report_plausible_rates():
     """fpdt_calibrate_mfma: every loop runs and the rates are ordered as the hardware orders them
     (MFMAs alone fastest; LDS-fed operands plus the softmax's vector work slowest), inside the
     range a 2.5 PFLOP/s part can deliver."""
-    rates = [B.fpdt_calibrate_mfma(kind, 2000)[0] for kind in range(len(B.FPDT_CAL_KINDS))]
+    rates = [B.fpdt_calibrate_mfma(kind, 8000)[0] for kind in range(len(B.FPDT_CAL_KINDS))]
     announce("calibration", dict(zip(B.FPDT_CAL_KINDS, (round(r) for r in rates))))
     assert all(300.0 < r < 2600.0 for r in rates)
     assert rates[0] > rates[2] > rates[6] and rates[0] > rates[4] > rates[6] and rates[1] > rates[7]
