@@ -14,15 +14,20 @@
  *   fpdt_tw_ffn_*          the feed-forward block, chunked with twice the attention's chunk
  *                          count, forward and (recomputing) backward.
  *
- * The dense products are plain library GEMMs (rocBLAS, bf16 inputs, fp32 accumulation); the
- * row-wise softmax / loss / gradient is a HIP kernel of this library.  Built as a separate
- * shared library (libfpdt_tokenwise.so) so that the attention library has no BLAS dependency.
+ * The dense products run on this library's own bf16 MFMA kernels (csrc/tw_gemm.hip: operands
+ * re-laid into MFMA fragments, 256 x 256 output tiles, fp32 accumulation); the row-wise softmax /
+ * loss / gradient and the activations are HIP kernels of this library as well.  Built as a
+ * separate shared library (libfpdt_tokenwise.so).
  *
  * Conventions as in fpdt.h: row-major contiguous tensors, device pointers, caller-owned
  * buffers, `stream` is a hipStream_t passed as void*, calls only enqueue, every function returns
- * an fpdt status code (0 = OK, 1 = invalid argument, 2 = unsupported, 3 = workspace, 4 = HIP or
- * rocBLAS failure; text from fpdt_tw_last_error).  The library creates one rocBLAS handle per
- * process on first use (rocBLAS may allocate its own device workspace).
+ * an fpdt status code (0 = OK, 1 = invalid argument, 2 = unsupported, 3 = workspace, 4 = HIP
+ * failure; text from fpdt_tw_last_error).  Besides the caller's workspace the library keeps one
+ * device scratch pool per GPU for the re-laid operands of the running call (weights once per
+ * call, activations per product); it grows on demand with hipMalloc -- so the first call of a
+ * given size must not run under stream capture -- and is kept until the process ends.  Calls
+ * that overlap in time on one GPU (different streams or threads) would share that pool: keep
+ * the library's calls on one stream.
  */
 #ifndef FPDT_TOKENWISE_H
 #define FPDT_TOKENWISE_H

@@ -15,9 +15,9 @@ SRC_DIR = os.path.join(PKG, "csrc")
 BUILD_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libfpdt.so")
 SOURCES = ["api.hip", "pack.hip", "fwd_bf16.hip", "bwd_bf16.hip", "f32_path.hip", "calibrate.hip"]
-# token-wise chunked neighbours (library GEMMs): a library of their own, linked against rocBLAS
+# token-wise chunked neighbours (projection, feed-forward block, loss): a library of their own
 TW_LIB = os.path.join(PKG, "libfpdt_tokenwise.so")
-TW_SOURCES = ["tokenwise.hip"]
+TW_SOURCES = ["tokenwise.hip", "tw_gemm.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops off: packed fp32 VALU forms are kept out of the generated code.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -40,7 +40,7 @@ def build(verbose: bool = False) -> str:
         objs = list(ex.map(_compile, SOURCES + TW_SOURCES))
     tw_objs = objs[len(SOURCES):]
     objs = objs[:len(SOURCES)]
-    for lib, o, extra in ((LIB, objs, []), (TW_LIB, tw_objs, ["-lrocblas"])):
+    for lib, o, extra in ((LIB, objs, []), (TW_LIB, tw_objs, [])):
         cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + o + extra
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:

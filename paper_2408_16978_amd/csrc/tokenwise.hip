@@ -1,7 +1,7 @@
 // Token-wise chunked neighbours of the attention path (Sec. 5.4): see include/fpdt_tokenwise.h.
-// Library GEMMs (rocBLAS) for the dense products, a HIP kernel for the row-wise softmax / loss.
+// The dense products are the MFMA kernels of tw_gemm.hip, the row-wise softmax / loss and the
+// activations are HIP kernels of this file.
 #include <hip/hip_runtime.h>
-#include <rocblas/rocblas.h>
 
 #include <cmath>
 #include <cstdarg>
@@ -10,6 +10,7 @@
 #include <string>
 
 #include "../../include/fpdt_tokenwise.h"
+#include "tw_gemm.h"
 
 namespace {
 
@@ -33,57 +34,45 @@ int fail(int code, const char* fmt, ...)
         hipError_t e_ = (expr);                                                                  \
         if (e_ != hipSuccess) return fail(TW_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
-#define BLAS_TRY(expr)                                                                            \
-    do {                                                                                          \
-        rocblas_status s_ = (expr);                                                               \
-        if (s_ != rocblas_status_success)                                                         \
-            return fail(TW_HIP, "%s failed: %s", #expr, rocblas_status_to_string(s_));            \
-    } while (0)
-
 std::mutex g_mu;
-rocblas_handle g_handle = nullptr;
 
-int get_handle(rocblas_handle* h, hipStream_t st)
+// The dense products are this library's own MFMA kernels (tw_gemm.hip).  A "handle" is just the
+// stream of the current call; taking it starts a call (packed weights of the previous call are
+// forgotten, its scratch is reused).
+struct GemmCtx { hipStream_t st; };
+typedef GemmCtx* gemm_handle;
+GemmCtx g_ctx;
+enum { TW_C_BF16 = 0, TW_C_F32 = 1 };
+
+int get_handle(gemm_handle* h, hipStream_t st)
 {
-    if (!g_handle) BLAS_TRY(rocblas_create_handle(&g_handle));
-    BLAS_TRY(rocblas_set_stream(g_handle, st));
-    BLAS_TRY(rocblas_set_pointer_mode(g_handle, rocblas_pointer_mode_host));
-    *h = g_handle;
+    g_ctx.st = st;
+    fpdt_tw::begin_call();
+    *h = &g_ctx;
     return TW_OK;
 }
 
-// Row-major C[M,N] (+)= alpha * A[M,K] * B^T where B is [N,K]  ("NT": both operands K-contiguous),
-// as the column-major product C^T[N,M] = B[N,K] ... expressed for rocBLAS:
-//   C_cm[N x M, ld N] = op(B_cm)[N x K] * A_cm[K x M], B_cm = B^T stored [K x N, ld K] -> transA = T.
-int gemm_nt(rocblas_handle h, int M, int N, int K, const void* A, const void* B, void* C,
-            rocblas_datatype c_type, float beta)
+int gemm_status(int rc)
 {
-    const float alpha = 1.f;
-    BLAS_TRY(rocblas_gemm_ex(h, rocblas_operation_transpose, rocblas_operation_none, N, M, K, &alpha, B,
-                             rocblas_datatype_bf16_r, K, A, rocblas_datatype_bf16_r, K, &beta, C, c_type, N, C,
-                             c_type, N, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0));
-    return TW_OK;
+    if (rc == 0) return TW_OK;
+    if (rc == 2) return fail(TW_UNSUPPORTED, "product beyond the launch limits");
+    return fail(TW_HIP, "GEMM launch or scratch allocation failed: %s", hipGetErrorString(hipGetLastError()));
 }
-// Row-major C[M,N] = A[M,K] * B[K,N]  ("NN"): C_cm[N x M] = B_cm[N x K, ld N] * A_cm[K x M, ld K].
-int gemm_nn(rocblas_handle h, int M, int N, int K, const void* A, const void* B, void* C,
-            rocblas_datatype c_type, float beta)
+
+// Row-major C[M,N] (+)= A[M,K] * B^T where B is [N,K]  ("NT": both operands K-contiguous); B is a weight.
+int gemm_nt(gemm_handle h, int M, int N, int K, const void* A, const void* B, void* C, int c_type, float beta)
 {
-    const float alpha = 1.f;
-    BLAS_TRY(rocblas_gemm_ex(h, rocblas_operation_none, rocblas_operation_none, N, M, K, &alpha, B,
-                             rocblas_datatype_bf16_r, N, A, rocblas_datatype_bf16_r, K, &beta, C, c_type, N, C,
-                             c_type, N, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0));
-    return TW_OK;
+    return gemm_status(fpdt_tw::gemm(0, 0, M, N, K, A, K, B, K, C, N, c_type == TW_C_F32, beta != 0.f, true, h->st));
 }
-// Row-major C[M,N] (+)= A^T * B with A [K,M], B [K,N]  ("TN": contraction over rows):
-//   C_cm[N x M] = B_cm[N x K, ld N] * (A_cm[M x K, ld M])^T.
-int gemm_tn(rocblas_handle h, int M, int N, int K, const void* A, const void* B, void* C,
-            rocblas_datatype c_type, float beta)
+// Row-major C[M,N] (+)= A[M,K] * B[K,N]  ("NN"); B is a weight, read transposed.
+int gemm_nn(gemm_handle h, int M, int N, int K, const void* A, const void* B, void* C, int c_type, float beta)
 {
-    const float alpha = 1.f;
-    BLAS_TRY(rocblas_gemm_ex(h, rocblas_operation_none, rocblas_operation_transpose, N, M, K, &alpha, B,
-                             rocblas_datatype_bf16_r, N, A, rocblas_datatype_bf16_r, M, &beta, C, c_type, N, C,
-                             c_type, N, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0));
-    return TW_OK;
+    return gemm_status(fpdt_tw::gemm(0, 1, M, N, K, A, K, B, N, C, N, c_type == TW_C_F32, beta != 0.f, true, h->st));
+}
+// Row-major C[M,N] (+)= A^T * B with A [K,M], B [K,N]  ("TN": contraction over rows, both per chunk).
+int gemm_tn(gemm_handle h, int M, int N, int K, const void* A, const void* B, void* C, int c_type, float beta)
+{
+    return gemm_status(fpdt_tw::gemm(1, 1, M, N, K, A, M, B, N, C, N, c_type == TW_C_F32, beta != 0.f, false, h->st));
 }
 
 __device__ __forceinline__ float wave_max(float v)
@@ -275,12 +264,12 @@ int fpdt_tw_linear_fwd(const void* X, const void* W, void* Y, int64_t rows, int 
     const int64_t c = (rows + n_chunks - 1) / n_chunks;
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g_mu);
-    rocblas_handle h;
+    gemm_handle h;
     if ((rc = get_handle(&h, st)) != TW_OK) return rc;
     for (int64_t r0 = 0; r0 < rows; r0 += c) {
         const int n = (int)(rows - r0 < c ? rows - r0 : c);
         rc = gemm_nt(h, n, n_out, n_in, static_cast<const char*>(X) + (size_t)r0 * n_in * 2, W,
-                     static_cast<char*>(Y) + (size_t)r0 * n_out * 2, rocblas_datatype_bf16_r, 0.f);
+                     static_cast<char*>(Y) + (size_t)r0 * n_out * 2, TW_C_BF16, 0.f);
         if (rc != TW_OK) return rc;
     }
     return TW_OK;
@@ -297,17 +286,17 @@ int fpdt_tw_linear_bwd(const void* X, const void* W, const void* dY, void* dX, f
     const int64_t c = (rows + n_chunks - 1) / n_chunks;
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g_mu);
-    rocblas_handle h;
+    gemm_handle h;
     if ((rc = get_handle(&h, st)) != TW_OK) return rc;
     for (int64_t r0 = 0; r0 < rows; r0 += c) {
         const int n = (int)(rows - r0 < c ? rows - r0 : c);
         const char* dYc = static_cast<const char*>(dY) + (size_t)r0 * n_out * 2;
         if (dX) {  // dX_c[n, n_in] = dY_c[n, n_out] W[n_out, n_in]
-            rc = gemm_nn(h, n, n_in, n_out, dYc, W, static_cast<char*>(dX) + (size_t)r0 * n_in * 2, rocblas_datatype_bf16_r, 0.f);
+            rc = gemm_nn(h, n, n_in, n_out, dYc, W, static_cast<char*>(dX) + (size_t)r0 * n_in * 2, TW_C_BF16, 0.f);
             if (rc != TW_OK) return rc;
         }
         if (dW) {  // dW[n_out, n_in] += dY_c^T X_c
-            rc = gemm_tn(h, n_out, n_in, n, dYc, static_cast<const char*>(X) + (size_t)r0 * n_in * 2, dW, rocblas_datatype_f32_r, 1.f);
+            rc = gemm_tn(h, n_out, n_in, n, dYc, static_cast<const char*>(X) + (size_t)r0 * n_in * 2, dW, TW_C_F32, 1.f);
             if (rc != TW_OK) return rc;
         }
     }
@@ -356,17 +345,17 @@ int fpdt_tw_ffn_fwd(const void* X, const void* W1, const void* W3, const void* W
     uint16_t* Hh = reinterpret_cast<uint16_t*>(ws + (sw ? 2 : 1) * t);
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g_mu);
-    rocblas_handle h;
+    gemm_handle h;
     if ((rc = get_handle(&h, st)) != TW_OK) return rc;
     for (int64_t r0 = 0; r0 < rows; r0 += c) {
         const int n = (int)(rows - r0 < c ? rows - r0 : c);
         const char* Xc = static_cast<const char*>(X) + (size_t)r0 * n_model * 2;
-        if ((rc = gemm_nt(h, n, n_ffn, n_model, Xc, W1, A, rocblas_datatype_bf16_r, 0.f)) != TW_OK) return rc;
-        if (sw && (rc = gemm_nt(h, n, n_ffn, n_model, Xc, W3, Bm, rocblas_datatype_bf16_r, 0.f)) != TW_OK) return rc;
+        if ((rc = gemm_nt(h, n, n_ffn, n_model, Xc, W1, A, TW_C_BF16, 0.f)) != TW_OK) return rc;
+        if (sw && (rc = gemm_nt(h, n, n_ffn, n_model, Xc, W3, Bm, TW_C_BF16, 0.f)) != TW_OK) return rc;
         const size_t ne = (size_t)n * n_ffn;
         ffn_act_kernel<<<dim3(ew_blocks(ne)), 256, 0, st>>>(A, Bm, Hh, ne, sw);
         if ((rc = gemm_nt(h, n, n_model, n_ffn, Hh, W2, static_cast<char*>(Y) + (size_t)r0 * n_model * 2,
-                          rocblas_datatype_bf16_r, 0.f)) != TW_OK) return rc;
+                          TW_C_BF16, 0.f)) != TW_OK) return rc;
     }
     HIP_TRY(hipGetLastError());
     return TW_OK;
@@ -389,7 +378,7 @@ int fpdt_tw_ffn_bwd(const void* X, const void* W1, const void* W3, const void* W
     uint16_t* dHh = reinterpret_cast<uint16_t*>(ws + (sw ? 3 : 2) * t);
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g_mu);
-    rocblas_handle h;
+    gemm_handle h;
     if ((rc = get_handle(&h, st)) != TW_OK) return rc;
     for (int64_t r0 = 0; r0 < rows; r0 += c) {
         const int n = (int)(rows - r0 < c ? rows - r0 : c);
@@ -398,21 +387,21 @@ int fpdt_tw_ffn_bwd(const void* X, const void* W1, const void* W3, const void* W
         char* dXc = static_cast<char*>(dX) + (size_t)r0 * n_model * 2;
         const size_t ne = (size_t)n * n_ffn;
         // recompute the chunk's pre-activations and hidden activations
-        if ((rc = gemm_nt(h, n, n_ffn, n_model, Xc, W1, A, rocblas_datatype_bf16_r, 0.f)) != TW_OK) return rc;
-        if (sw && (rc = gemm_nt(h, n, n_ffn, n_model, Xc, W3, Bm, rocblas_datatype_bf16_r, 0.f)) != TW_OK) return rc;
+        if ((rc = gemm_nt(h, n, n_ffn, n_model, Xc, W1, A, TW_C_BF16, 0.f)) != TW_OK) return rc;
+        if (sw && (rc = gemm_nt(h, n, n_ffn, n_model, Xc, W3, Bm, TW_C_BF16, 0.f)) != TW_OK) return rc;
         if (dW2) {
             ffn_act_kernel<<<dim3(ew_blocks(ne)), 256, 0, st>>>(A, Bm, Hh, ne, sw);
             // dW2[n_model, n_ffn] += dY_c^T Hh
-            if ((rc = gemm_tn(h, n_model, n_ffn, n, dYc, Hh, dW2, rocblas_datatype_f32_r, 1.f)) != TW_OK) return rc;
+            if ((rc = gemm_tn(h, n_model, n_ffn, n, dYc, Hh, dW2, TW_C_F32, 1.f)) != TW_OK) return rc;
         }
         // dHh[n, n_ffn] = dY_c[n, n_model] W2[n_model, n_ffn]
-        if ((rc = gemm_nn(h, n, n_ffn, n_model, dYc, W2, dHh, rocblas_datatype_bf16_r, 0.f)) != TW_OK) return rc;
+        if ((rc = gemm_nn(h, n, n_ffn, n_model, dYc, W2, dHh, TW_C_BF16, 0.f)) != TW_OK) return rc;
         ffn_act_grad_kernel<<<dim3(ew_blocks(ne)), 256, 0, st>>>(A, Bm, dHh, ne, sw);  // A <- dA, B <- dB
         // dX_c = dA W1 (+ dB W3)
-        if ((rc = gemm_nn(h, n, n_model, n_ffn, A, W1, dXc, rocblas_datatype_bf16_r, 0.f)) != TW_OK) return rc;
-        if (sw && (rc = gemm_nn(h, n, n_model, n_ffn, Bm, W3, dXc, rocblas_datatype_bf16_r, 1.f)) != TW_OK) return rc;
-        if (dW1 && (rc = gemm_tn(h, n_ffn, n_model, n, A, Xc, dW1, rocblas_datatype_f32_r, 1.f)) != TW_OK) return rc;
-        if (sw && dW3 && (rc = gemm_tn(h, n_ffn, n_model, n, Bm, Xc, dW3, rocblas_datatype_f32_r, 1.f)) != TW_OK) return rc;
+        if ((rc = gemm_nn(h, n, n_model, n_ffn, A, W1, dXc, TW_C_BF16, 0.f)) != TW_OK) return rc;
+        if (sw && (rc = gemm_nn(h, n, n_model, n_ffn, Bm, W3, dXc, TW_C_BF16, 1.f)) != TW_OK) return rc;
+        if (dW1 && (rc = gemm_tn(h, n_ffn, n_model, n, A, Xc, dW1, TW_C_F32, 1.f)) != TW_OK) return rc;
+        if (sw && dW3 && (rc = gemm_tn(h, n_ffn, n_model, n, Bm, Xc, dW3, TW_C_F32, 1.f)) != TW_OK) return rc;
     }
     HIP_TRY(hipGetLastError());
     return TW_OK;
@@ -447,24 +436,24 @@ int fpdt_tw_loss_fwd_bwd(const void* H, const void* W, const int32_t* target, fl
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g_mu);
-    rocblas_handle h;
+    gemm_handle h;
     int rc = get_handle(&h, st);
     if (rc != TW_OK) return rc;
     for (int64_t r0 = 0; r0 < rows; r0 += c) {
         const int n = (int)(rows - r0 < c ? rows - r0 : c);
         const char* Hc = static_cast<const char*>(H) + (size_t)r0 * hidden * 2;
         // logits[n, vocab] = H_c W^T
-        rc = gemm_nt(h, n, vocab, hidden, Hc, W, logits, rocblas_datatype_f32_r, 0.f);
+        rc = gemm_nt(h, n, vocab, hidden, Hc, W, logits, TW_C_F32, 0.f);
         if (rc != TW_OK) return rc;
         loss_rows_kernel<<<dim3((unsigned)n), 256, 0, st>>>(logits, target + r0, vocab, grad_scale, loss + r0, lse + r0,
                                                              bwd ? G : nullptr);
         if (dH) {  // dH_c[n, hidden] = G[n, vocab] W[vocab, hidden]
             rc = gemm_nn(h, n, hidden, vocab, G, W, static_cast<char*>(dH) + (size_t)r0 * hidden * 2,
-                         rocblas_datatype_bf16_r, 0.f);
+                         TW_C_BF16, 0.f);
             if (rc != TW_OK) return rc;
         }
         if (dW) {  // dW[vocab, hidden] += G^T[vocab, n] H_c[n, hidden]
-            rc = gemm_tn(h, vocab, hidden, n, G, Hc, dW, rocblas_datatype_f32_r, 1.f);
+            rc = gemm_tn(h, vocab, hidden, n, G, Hc, dW, TW_C_F32, 1.f);
             if (rc != TW_OK) return rc;
         }
     }

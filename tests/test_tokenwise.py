@@ -390,7 +390,7 @@ def test_gpu_tokenwise_calls_replay_from_a_graph():
         for n, t in outs.items():
             t.zero_() if n.startswith("dW") else t.fill_(float("nan"))
 
-    step()  # first call: creates the rocBLAS handle and loads its kernels outside any capture
+    step()  # first call: sizes the library's operand scratch pool and loads its kernels outside any capture
     reset()
     step()
     torch.cuda.synchronize()
