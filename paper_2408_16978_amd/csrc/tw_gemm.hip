@@ -90,7 +90,10 @@ constexpr int TILE = 256;                  // output tile: 8 row blocks x 8 colu
 #define FPDT_TW_SKT 4
 #endif
 constexpr int SKT = FPDT_TW_SKT;           // k-steps of 16 per LDS stage (the packed k is a multiple of 64)
-constexpr int RING = SKT == 2 ? 3 : 2;     // 32 KiB stages: three slots, two stages ahead; 64 KiB stages: two slots
+#ifndef FPDT_TW_RING
+#define FPDT_TW_RING (FPDT_TW_SKT == 2 ? 3 : 2)
+#endif
+constexpr int RING = FPDT_TW_RING;         // LDS slots of one stage each; RING - 1 stages are requested ahead
 constexpr int OP_U4 = 8 * SKT * 64;        // one operand of a stage
 constexpr int STAGE_U4 = 2 * OP_U4;
 constexpr int NCOPY = (2 * 8 * SKT) / NWAVE;  // fragments a wave copies per stage
