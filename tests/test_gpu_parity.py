@@ -267,3 +267,18 @@ def test_calibration_loops_report_plausible_rates():
     announce("calibration", dict(zip(B.FPDT_CAL_KINDS, (round(r) for r in rates))))
     assert all(300.0 < r < 2600.0 for r in rates)
     assert max(rates[6], rates[7]) < 0.95 * max(rates[0], rates[1])
+
+
+@pytest.mark.parametrize("flags", [0, B.FPDT_BWD_STORE_DS, B.FPDT_KV_ON_HOST | B.FPDT_BWD_STORE_DS])
+def test_results_are_reproducible_bit_for_bit(flags):
+    """No atomics and no order that depends on timing anywhere on the path: two runs of the same
+    problem (buffers allocated afresh, so at other addresses) give the same bits."""
+    S, chunk, Hq, Hkv, D = 4096, 1024, 8, 2, 128
+    announce("reproducibility", S, chunk, flags)
+    Q, K, V, dO = inputs.make_qkvdo(S, Hq, Hkv, D, "bf16", seed=16)
+    first = {n: t.clone() for n, t in run(Q, K, V, dO, chunk, D ** -0.5, flags).items()}
+    pad = torch.empty(3 << 20, dtype=torch.uint8, device="cuda")  # shifts the next allocations
+    second = run(Q, K, V, dO, chunk, D ** -0.5, flags)
+    for n in ("O", "LSE", "dQ", "dK", "dV"):
+        assert torch.equal(first[n].cpu(), second[n].cpu()), n
+    del pad
