@@ -94,9 +94,7 @@ constexpr int SKT = FPDT_TW_SKT;           // k-steps of 16 per LDS stage (the p
 #define FPDT_TW_RING (FPDT_TW_SKT == 2 ? 3 : 2)
 #endif
 constexpr int RING = FPDT_TW_RING;         // LDS slots of one stage each; RING - 1 stages are requested ahead
-constexpr int OP_U4 = 8 * SKT * 64;        // one operand of a stage
-constexpr int STAGE_U4 = 2 * OP_U4;
-constexpr int NCOPY = (2 * 8 * SKT) / NWAVE;  // fragments a wave copies per stage
+constexpr int OP_U4 = 8 * SKT * 64;        // the B operand of a stage (8 column blocks); A has 2 WMT row blocks
 
 __device__ __forceinline__ uint16_t to_bf16(float f)
 {
@@ -106,15 +104,22 @@ __device__ __forceinline__ uint16_t to_bf16(float f)
 }
 __device__ __forceinline__ float from_bf16(uint16_t b) { return __uint_as_float((unsigned)b << 16); }
 
-// Af, Bf: packed operands (row blocks padded to a multiple of 8, KT even).  C [M, N] row-major,
-// leading dimension ldc elements.  Workgroup = 8 waves; wave (wm, wn) = (w / 4, w % 4) owns rows
-// 128 wm .. +127 and columns 64 wn .. +63 of the tile: 4 x 2 accumulator tiles, every A fragment
-// read from LDS feeds two MFMAs and every B fragment four (0.75 fragments per MFMA).
-template <bool OUT_F32, bool ACCUM>
+// Af, Bf: packed operands (row blocks padded to a multiple of 8, KT a multiple of SKT).  C [M, N]
+// row-major, leading dimension ldc elements.  Workgroup = 8 waves; wave (wm, wn) = (w / 4, w % 4)
+// owns rows 32 WMT wm .. and columns 64 wn .. +63 of a (64 WMT) x 256 tile: WMT x 2 accumulator
+// tiles.  WMT = 4 (256 x 256 tiles): every A fragment read from LDS feeds two MFMAs and every B
+// fragment four, 0.75 fragments per MFMA; WMT = 2, 1 (128 and 64 rows) are for products with so
+// few rows that the large tiles would leave most of the chip idle.
+template <bool OUT_F32, bool ACCUM, int WMT>
 __global__ __launch_bounds__(NTHREAD) void tw_gemm_kernel(const u32x4* __restrict__ Af, const u32x4* __restrict__ Bf,
                                                            int KT, void* __restrict__ Cout, int64_t ldc, int M, int N,
                                                            int tiles_n, int tiles_total)
 {
+    constexpr int AOP_U4 = 2 * WMT * SKT * 64;              // the A operand of a stage
+    constexpr int STAGE_U4 = AOP_U4 + OP_U4;
+    constexpr int NFRAG = (2 * WMT + 8) * SKT;              // fragments of a stage
+    constexpr int NCOPY = NFRAG / NWAVE;                    // copied by each wave
+    static_assert(NFRAG % NWAVE == 0, "every wave copies the same number of fragments");
     __shared__ u32x4 ring[RING][STAGE_U4];
     // Consecutive workgroup ids land on different XCDs (each with its own L2): give every XCD a
     // contiguous run of tiles, so that the tiles that share an operand row share an L2.
@@ -135,22 +140,23 @@ __global__ __launch_bounds__(NTHREAD) void tw_gemm_kernel(const u32x4* __restric
     const int wm = wu >> 2, wn = wu & 3;
     const int n_stages = KT / SKT;
 
-    const u32x4* abase = Af + (size_t)tile_m * 8 * KT * 64;
+    const u32x4* abase = Af + (size_t)tile_m * (2 * WMT) * KT * 64;
     const u32x4* bbase = Bf + (size_t)tile_n * 8 * KT * 64;
     // stage s into a slot: fragment f = wave + 8 j of the stage's 16 SKT (operand, block, k-step)
     auto issue = [&](int s, u32x4* slot) {
 #pragma unroll
         for (int j = 0; j < NCOPY; ++j) {
-            const int f = wu + NWAVE * j;
-            const int op = f / (8 * SKT), blk = (f / SKT) & 7, kt = f % SKT;
-            const u32x4* src = (op ? bbase : abase) + ((size_t)blk * KT + (size_t)s * SKT + kt) * 64;
-            fpdt::frag_to_lds(src, slot + op * OP_U4 + (blk * SKT + kt) * 64, lane);
+            const int f = wu + NWAVE * j;                        // A fragments first, then B
+            const bool isb = f >= 2 * WMT * SKT;
+            const int g = isb ? f - 2 * WMT * SKT : f, blk = g / SKT, kt = g % SKT;
+            const u32x4* src = (isb ? bbase : abase) + ((size_t)blk * KT + (size_t)s * SKT + kt) * 64;
+            fpdt::frag_to_lds(src, slot + (isb ? AOP_U4 : 0) + g * 64, lane);
         }
     };
 
-    floatx16 acc[4][2];
+    floatx16 acc[WMT][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WMT; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -167,13 +173,13 @@ __global__ __launch_bounds__(NTHREAD) void tw_gemm_kernel(const u32x4* __restric
         if (s + PF < n_stages) issue(s + PF, ring[pf_i]);
 #pragma unroll
         for (int kt = 0; kt < SKT; ++kt) {
-            bf16x8 a[4], b[2];
+            bf16x8 a[WMT], b[2];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = fpdt::as_bf16x8(slot[((wm * 4 + i) * SKT + kt) * 64 + lane]);
+            for (int i = 0; i < WMT; ++i) a[i] = fpdt::as_bf16x8(slot[((wm * WMT + i) * SKT + kt) * 64 + lane]);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = fpdt::as_bf16x8(slot[OP_U4 + ((wn * 2 + j) * SKT + kt) * 64 + lane]);
+            for (int j = 0; j < 2; ++j) b[j] = fpdt::as_bf16x8(slot[AOP_U4 + ((wn * 2 + j) * SKT + kt) * 64 + lane]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < WMT; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) acc[i][j] = fpdt::mfma32(a[i], b[j], acc[i][j]);
         }
@@ -188,14 +194,14 @@ __global__ __launch_bounds__(NTHREAD) void tw_gemm_kernel(const u32x4* __restric
     // accumulator tile (i, j): lane l holds column l % 32, register r row 8 (r / 4) + 4 (l / 32) + r % 4
     const int col = lane & 31, half = lane >> 5;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WMT; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int n = tile_n * TILE + wn * 64 + j * 32 + col;
             if (n < N) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int m = tile_m * TILE + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const int m = tile_m * (64 * WMT) + wm * (32 * WMT) + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                     if (m < M) {
                         const size_t at = (size_t)m * ldc + n;
                         if (OUT_F32) {
@@ -310,18 +316,29 @@ int gemm(int a_transposed, int b_transposed, int M, int N, int K, const void* A,
     const size_t mark = pool.off;  // what follows is scratch of this product only
     rc = pack_operand(pool, A, a_transposed ? K : M, a_transposed ? M : K, lda, a_transposed, false, st, &pa);
     if (rc) return rc;
-    const int tiles_m = (M + TILE - 1) / TILE, tiles_n = (N + TILE - 1) / TILE;
+    // 256-row tiles unless they would leave most of the chip idle: then 128 or 64 rows per tile
+    const int tiles_n = (N + TILE - 1) / TILE;
+    int wmt = 4;
+    while (wmt > 1 && (long long)((M + 64 * wmt - 1) / (64 * wmt)) * tiles_n < 256) wmt /= 2;
+    const int tiles_m = (M + 64 * wmt - 1) / (64 * wmt);
     const long long total = (long long)tiles_m * tiles_n;
     if (total > (1ll << 30)) return 2;
     const unsigned grid = (unsigned)((total + 7) / 8 * 8);
     const int KT = pa.KT;  // = pb.KT: both contract over K
+#define TW_LAUNCH(F32, ACC)                                                                                                   \
+    do {                                                                                                                      \
+        if (wmt == 4) tw_gemm_kernel<F32, ACC, 4><<<grid, NTHREAD, 0, st>>>(pa.frags, pb.frags, KT, C, ldc, M, N, tiles_n, (int)total);      \
+        else if (wmt == 2) tw_gemm_kernel<F32, ACC, 2><<<grid, NTHREAD, 0, st>>>(pa.frags, pb.frags, KT, C, ldc, M, N, tiles_n, (int)total); \
+        else tw_gemm_kernel<F32, ACC, 1><<<grid, NTHREAD, 0, st>>>(pa.frags, pb.frags, KT, C, ldc, M, N, tiles_n, (int)total);               \
+    } while (0)
     if (c_f32) {
-        if (accumulate) tw_gemm_kernel<true, true><<<grid, NTHREAD, 0, st>>>(pa.frags, pb.frags, KT, C, ldc, M, N, tiles_n, (int)total);
-        else tw_gemm_kernel<true, false><<<grid, NTHREAD, 0, st>>>(pa.frags, pb.frags, KT, C, ldc, M, N, tiles_n, (int)total);
+        if (accumulate) TW_LAUNCH(true, true);
+        else TW_LAUNCH(true, false);
     } else {
-        if (accumulate) tw_gemm_kernel<false, true><<<grid, NTHREAD, 0, st>>>(pa.frags, pb.frags, KT, C, ldc, M, N, tiles_n, (int)total);
-        else tw_gemm_kernel<false, false><<<grid, NTHREAD, 0, st>>>(pa.frags, pb.frags, KT, C, ldc, M, N, tiles_n, (int)total);
+        if (accumulate) TW_LAUNCH(false, true);
+        else TW_LAUNCH(false, false);
     }
+#undef TW_LAUNCH
     // The next product's packs run after this launch on the same stream, so this product's scratch
     // is free again: everything it took, or everything behind a weight that stays cached.  (Not if
     // the pool was replaced by a larger one on the way: then nothing is given back until the next
