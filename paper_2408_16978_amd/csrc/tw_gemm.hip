@@ -90,6 +90,9 @@ constexpr int TILE = 256;                  // output tile: 8 row blocks x 8 colu
 #define FPDT_TW_SKT 4
 #endif
 constexpr int SKT = FPDT_TW_SKT;           // k-steps of 16 per LDS stage (the packed k is a multiple of 64)
+#ifndef FPDT_TW_ISSUE_LATE
+#define FPDT_TW_ISSUE_LATE 0
+#endif
 #ifndef FPDT_TW_RING
 #define FPDT_TW_RING (FPDT_TW_SKT == 2 ? 3 : 2)
 #endif
@@ -170,9 +173,16 @@ __global__ __launch_bounds__(NTHREAD) void tw_gemm_kernel(const u32x4* __restric
     int slot_i = 0, pf_i = PF % RING;
     for (int s = 0; s < n_stages; ++s) {
         const u32x4* slot = ring[slot_i];
+#if FPDT_TW_ISSUE_LATE == 0
         if (s + PF < n_stages) issue(s + PF, ring[pf_i]);
+#endif
 #pragma unroll
         for (int kt = 0; kt < SKT; ++kt) {
+#if FPDT_TW_ISSUE_LATE
+            // the copies go out behind the first k-step's MFMAs: right after the barrier every wave
+            // of the workgroup would issue them at the same time, with no MFMA in flight
+            if (kt == 1 && s + PF < n_stages) issue(s + PF, ring[pf_i]);
+#endif
             bf16x8 a[WMT], b[2];
 #pragma unroll
             for (int i = 0; i < WMT; ++i) a[i] = fpdt::as_bf16x8(slot[((wm * WMT + i) * SKT + kt) * 64 + lane]);
